@@ -1,0 +1,123 @@
+/*
+ * tbe355 - table-batched embedding forward and fused sparse backward with moment-scaled row-wise
+ * AdaGrad, for one MI355X (gfx950).  C ABI: plain pointers and sizes, status codes, no exceptions.
+ *
+ * The operation is the per-GPU embedding step of a sharded recommendation model: every GPU looks up
+ * the ids of the batch in the table shards it hosts and, in the backward pass, turns the gradients of
+ * the rows that appeared in the batch into an immediate optimizer step, so that no gradient tensor is
+ * ever materialised (paper, Section 2.1 and Section 3.1: the backward pass and the optimizer of the
+ * sparse tables are fused).  The optimizer is the paper's moment-scaled row-wise AdaGrad
+ * (Algorithm 1, steps 5 and 6).
+ *
+ * Conventions
+ *   - T tables; table t has rows[t] rows of D[t] columns.  All tables live in ONE flat device buffer,
+ *     table after table, each row-major; element offset of table t is sum_{u<t} rows[u]*D[u].
+ *   - A batch has B samples.  Bag (t, b) is the list of ids of table t for sample b.  Ids are
+ *     table-local, in [0, rows[t]).  Layout is table-major CSR: bag (t, b) owns
+ *     indices[offsets[t*B + b] .. offsets[t*B + b + 1]).  offsets has T*B + 1 entries, offsets[0] = 0,
+ *     offsets[T*B] = nnz.  The same id may occur several times in a bag and counts every time.
+ *   - Pooled output / upstream gradient: float32 [B, sum(D)] row-major; bag (t, b) maps to columns
+ *     D_offsets[t] .. D_offsets[t+1]-1 of row b.
+ *   - Every pointer argument marked DEVICE is device memory owned by the caller; HOST pointers are read
+ *     during the call only.  The library allocates device memory only in tbe_create (a few KB of table
+ *     metadata) and never in the two hot calls.
+ *   - The hot calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and return without synchronising.  They are safe to capture into a HIP graph.
+ *   - Limits: 4 <= D[t] <= 1024 and D[t] % 4 == 0 (% 8 for fp16 weights); rows[t] < 2^31;
+ *     sum(rows) < 2^32 - 1; nnz < 2^32 - 1; T*B < 2^31.
+ *   - Errors are returned as tbe_status; nothing is launched when an argument check fails.  An id
+ *     outside its table never causes an out-of-bounds access: the forward skips it, the backward gives
+ *     it to no row, and both raise a sticky device flag that tbe_poll_index_error reads back.
+ */
+#ifndef TBE355_H
+#define TBE355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tbe_handle tbe_handle; /* opaque: table shapes + small device-side metadata + timing events */
+
+typedef enum {
+    TBE_OK = 0,
+    TBE_EINVAL = 1,     /* NULL / misaligned pointer, non-finite or out-of-range scalar */
+    TBE_ESHAPE = 2,     /* a size outside the limits above */
+    TBE_EDTYPE = 3,     /* unknown dtype or pooling code */
+    TBE_EWORKSPACE = 4, /* workspace smaller than tbe_workspace_bytes says */
+    TBE_EINDEX = 5,     /* an id outside its table was seen (reported by tbe_poll_index_error) */
+    TBE_EHIP = 6        /* a HIP runtime call failed */
+} tbe_status;
+
+typedef enum { TBE_F32 = 0, TBE_F16 = 1 } tbe_dtype;    /* storage type of the tables; math is fp32 */
+typedef enum { TBE_SUM = 0, TBE_MEAN = 1 } tbe_pooling; /* mean divides a bag's sum by its length */
+
+/* Describe the table set.  rows, D: HOST arrays of T entries.  Builds D_offsets / row_base / table
+ * offsets on the current device.  The handle can be used by one stream at a time. */
+tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtype weight_dtype, tbe_handle** out);
+tbe_status tbe_destroy(tbe_handle* h);
+
+/* Bytes of scratch that tbe_backward_rowwise_adagrad needs for a batch of B samples and at most
+ * max_nnz lookups (sort double buffers, segment lists, partial sums of very hot rows). */
+tbe_status tbe_workspace_bytes(const tbe_handle* h, int32_t B, int64_t max_nnz, size_t* bytes);
+
+/* Forward: pooled lookup (paper Section 2.1: an id selects a row of its table; the problem statement
+ * pools a bag of rows by sum or mean).
+ *   out[b, D_offsets[t] + j] = s * sum_{p in bag (t,b)} tables_t[indices[p], j],  s = 1 (sum) or 1/len (mean);
+ * an empty bag gives zeros.  fp32 accumulation.
+ *   tables    DEVICE  flat weights (float or IEEE binary16 per the handle's dtype), 16-byte aligned
+ *   D_offsets DEVICE  int32 [T+1], or NULL to use the handle's own copy
+ *   indices   DEVICE  int64 [nnz];  offsets DEVICE int64 [T*B+1]
+ *   out       DEVICE  float [B, sum(D)], 16-byte aligned, fully overwritten */
+tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const int64_t* indices,
+                       const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
+                       void* hip_stream);
+
+/* Backward + optimizer, in place (paper Section 2.1: only rows whose ids appear in the batch get a
+ * gradient; Section 3.2: a row's gradient is the sum over the samples that hit it; Algorithm 1 steps 5-6).
+ * Steps: key[p] = row_base[table of p] + indices[p]; stable ascending radix sort of (key, p);
+ * run-length segmentation into unique rows; per unique row u of table t
+ *   g      = sum over the row's segment of  s_bag * grad_out[b, D_offsets[t] : D_offsets[t+1]]
+ *   v_u    = v_u + ||g||_2^2                       (state, stored unscaled)
+ *   w_u   -= lr / (sqrt(v_u / momentum_scale) + eps) * g      (uses the updated v_u)
+ * exactly once per unique row; every other row of tables/state keeps its bits.  momentum_scale is the
+ * paper's scaling factor c (> 0); c = 1 is plain row-wise AdaGrad.  Results do not depend on timing:
+ * no floating-point atomics are used, so two runs on the same inputs agree bit for bit.
+ *   grad_out  DEVICE float [B, sum(D)], 16-byte aligned
+ *   tables    DEVICE in/out;  state DEVICE float [sum(rows)] in/out, indexed by linearised row key
+ *   workspace DEVICE, 256-byte aligned, >= tbe_workspace_bytes(h, B, nnz); contents are scratch */
+tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
+                                        const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
+                                        float eps, float momentum_scale, void* tables, float* state, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream);
+
+/* Parity hooks: DEVICE pointers into `workspace` holding the integer by-products of the last backward
+ * call made with the same (h, workspace, B, nnz); valid until the next backward on that workspace.
+ *   keys_sorted[nnz], vals_sorted[nnz] (original positions p, ascending inside a run of equal keys),
+ *   unique_rows[*num_unique] ascending, seg_start[*num_unique + 1] (seg_start[U] = nnz), num_unique[1].
+ * Invalid ids, if any, appear as one trailing pseudo-row with key sum(rows). */
+tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int64_t nnz,
+                            const uint32_t** keys_sorted, const uint32_t** vals_sorted, const uint32_t** unique_rows,
+                            const uint32_t** seg_start, const uint32_t** num_unique);
+
+/* Synchronises the device, reads and clears the sticky invalid-id flag.  Returns TBE_EINDEX if it was set. */
+tbe_status tbe_poll_index_error(tbe_handle* h);
+
+/* Per-kernel timing with HIP events on the stream the kernels run on.  tbe_timing_enable(h, 1) clears
+ * the record and turns timing on: from then on every kernel that a forward/backward call launches is
+ * bracketed by two events and appended to the record, in launch order.  tbe_timing_count gives the
+ * number of recorded launches; tbe_timing_read synchronises on launch i's events and returns the
+ * kernel's name (a static string) and its duration in milliseconds.  tbe_timing_enable(h, 0) turns it
+ * off.  Do not enable while capturing a graph. */
+tbe_status tbe_timing_enable(tbe_handle* h, int enable);
+tbe_status tbe_timing_count(tbe_handle* h, int32_t* n);
+tbe_status tbe_timing_read(tbe_handle* h, int32_t i, const char** name, float* ms);
+
+const char* tbe_status_string(tbe_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBE355_H */

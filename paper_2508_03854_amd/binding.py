@@ -1,0 +1,220 @@
+"""Thin ctypes binding of libtbe355.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory and streams.  There is no fallback: if the HIP library is missing or a
+call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import torch  # must be imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtbe355.so")
+
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, EINDEX, EHIP = range(7)
+F32, F16 = 0, 1
+SUM, MEAN = 0, 1
+
+# every symbol include/tbe355.h declares
+EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
+           "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable", "tbe_timing_count", "tbe_timing_read",
+           "tbe_status_string"]
+
+
+class TbeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({_status_string(status)})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libtbe355.so; raises if it has not been built (python -m paper_2508_03854_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} is missing: build it with `python paper_2508_03854_amd/build.py`")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.tbe_create.restype = ctypes.c_int
+    L.tbe_create.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.c_int, ctypes.POINTER(vp)]
+    L.tbe_destroy.restype = ctypes.c_int
+    L.tbe_destroy.argtypes = [vp]
+    L.tbe_workspace_bytes.restype = ctypes.c_int
+    L.tbe_workspace_bytes.argtypes = [vp, i32, i64, ctypes.POINTER(ctypes.c_size_t)]
+    L.tbe_forward.restype = ctypes.c_int
+    L.tbe_forward.argtypes = [vp, vp, vp, vp, vp, i32, i64, ctypes.c_int, vp, vp]
+    L.tbe_backward_rowwise_adagrad.restype = ctypes.c_int
+    L.tbe_backward_rowwise_adagrad.argtypes = [vp, vp, vp, vp, i32, i64, ctypes.c_int, f32, f32, f32, vp, vp, vp,
+                                               ctypes.c_size_t, vp]
+    L.tbe_debug_sorted.restype = ctypes.c_int
+    L.tbe_debug_sorted.argtypes = [vp, vp, i32, i64] + [ctypes.POINTER(vp)] * 5
+    L.tbe_poll_index_error.restype = ctypes.c_int
+    L.tbe_poll_index_error.argtypes = [vp]
+    L.tbe_timing_enable.restype = ctypes.c_int
+    L.tbe_timing_enable.argtypes = [vp, ctypes.c_int]
+    L.tbe_timing_count.restype = ctypes.c_int
+    L.tbe_timing_count.argtypes = [vp, ctypes.POINTER(i32)]
+    L.tbe_timing_read.restype = ctypes.c_int
+    L.tbe_timing_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(f32)]
+    L.tbe_status_string.restype = ctypes.c_char_p
+    L.tbe_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def _status_string(s: int) -> str:
+    try:
+        return load_library().tbe_status_string(int(s)).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise TbeError(status, what)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype: torch.dtype, what: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+class TBE:
+    """One table set (tbe_handle).  Methods mirror the C entry points one to one."""
+
+    def __init__(self, rows: Sequence[int], D: Sequence[int], weight_dtype: str = "f32"):
+        self._lib = load_library()
+        self.rows = [int(r) for r in rows]
+        self.D = [int(d) for d in D]
+        self.T = len(self.rows)
+        assert len(self.D) == self.T
+        self.weight_dtype = weight_dtype
+        self.torch_dtype = {"f32": torch.float32, "f16": torch.float16}[weight_dtype]
+        self.sum_D = sum(self.D)
+        self.total_rows = sum(self.rows)
+        self.total_elems = sum(r * d for r, d in zip(self.rows, self.D))
+        rows_a = (ctypes.c_int64 * self.T)(*self.rows)
+        D_a = (ctypes.c_int32 * self.T)(*self.D)
+        h = ctypes.c_void_p()
+        _check(self._lib.tbe_create(self.T, rows_a, D_a, {"f32": F32, "f16": F16}[weight_dtype], ctypes.byref(h)),
+               "tbe_create")
+        self._h = h
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._lib.tbe_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- tbe_workspace_bytes
+    def workspace_bytes(self, B: int, max_nnz: int) -> int:
+        n = ctypes.c_size_t()
+        _check(self._lib.tbe_workspace_bytes(self._h, int(B), int(max_nnz), ctypes.byref(n)), "tbe_workspace_bytes")
+        return int(n.value)
+
+    def alloc_workspace(self, B: int, max_nnz: int, device="cuda") -> torch.Tensor:
+        return torch.empty(self.workspace_bytes(B, max_nnz), dtype=torch.uint8, device=device)
+
+    # ---- tbe_forward
+    def forward(self, tables: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int, pooling: str = "sum",
+                out: Optional[torch.Tensor] = None, D_offsets: Optional[torch.Tensor] = None,
+                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(B, self.sum_D, dtype=torch.float32, device=tables.device)
+        if tables.numel() != self.total_elems or out.shape != (B, self.sum_D):
+            raise ValueError("tables / out shape does not match the handle")
+        if offsets.numel() != self.T * B + 1:
+            raise ValueError("offsets must have T*B+1 entries")
+        nnz = indices.numel()
+        st = self._lib.tbe_forward(self._h, _dev_ptr(tables, self.torch_dtype, "tables"),
+                                   _dev_ptr(D_offsets, torch.int32, "D_offsets"),
+                                   _dev_ptr(indices, torch.int64, "indices"), _dev_ptr(offsets, torch.int64, "offsets"),
+                                   int(B), int(nnz), {"sum": SUM, "mean": MEAN}[pooling],
+                                   _dev_ptr(out, torch.float32, "out"), _stream_ptr(stream))
+        _check(st, "tbe_forward")
+        return out
+
+    # ---- tbe_backward_rowwise_adagrad
+    def backward_rowwise_adagrad(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,
+                                 tables: torch.Tensor, state: torch.Tensor, workspace: torch.Tensor, *,
+                                 pooling: str = "sum", lr: float, eps: float, momentum_scale: float = 1.0,
+                                 stream: Optional[torch.cuda.Stream] = None) -> None:
+        if tables.numel() != self.total_elems or state.numel() != self.total_rows:
+            raise ValueError("tables / state shape does not match the handle")
+        if grad_out.shape != (B, self.sum_D) or offsets.numel() != self.T * B + 1:
+            raise ValueError("grad_out / offsets shape does not match the handle")
+        nnz = indices.numel()
+        st = self._lib.tbe_backward_rowwise_adagrad(
+            self._h, _dev_ptr(grad_out, torch.float32, "grad_out"), _dev_ptr(indices, torch.int64, "indices"),
+            _dev_ptr(offsets, torch.int64, "offsets"), int(B), int(nnz), {"sum": SUM, "mean": MEAN}[pooling],
+            float(lr), float(eps), float(momentum_scale), _dev_ptr(tables, self.torch_dtype, "tables"),
+            _dev_ptr(state, torch.float32, "state"), _dev_ptr(workspace, torch.uint8, "workspace"),
+            int(workspace.numel()), _stream_ptr(stream))
+        _check(st, "tbe_backward_rowwise_adagrad")
+
+    # ---- tbe_debug_sorted
+    def debug_sorted(self, workspace: torch.Tensor, B: int, nnz: int) -> Dict[str, torch.Tensor]:
+        """Copies the integer by-products of the last backward to host tensors (int64; synchronises)."""
+        ptrs = [ctypes.c_void_p() for _ in range(5)]
+        _check(self._lib.tbe_debug_sorted(self._h, workspace.data_ptr(), int(B), int(nnz),
+                                          *[ctypes.byref(p) for p in ptrs]), "tbe_debug_sorted")
+        base = workspace.data_ptr()
+        torch.cuda.synchronize()
+
+        def view(p: ctypes.c_void_p, n: int) -> torch.Tensor:
+            off = p.value - base
+            return workspace[off:off + 4 * n].view(torch.int32).cpu().to(torch.int64) & 0xFFFFFFFF
+
+        U = int(view(ptrs[4], 1).item())
+        return {"keys_sorted": view(ptrs[0], nnz), "vals_sorted": view(ptrs[1], nnz),
+                "unique_rows": view(ptrs[2], U), "seg_start": view(ptrs[3], U + 1), "num_unique": U}
+
+    # ---- tbe_poll_index_error
+    def poll_index_error(self) -> bool:
+        st = self._lib.tbe_poll_index_error(self._h)
+        if st == EINDEX:
+            return True
+        _check(st, "tbe_poll_index_error")
+        return False
+
+    # ---- tbe_timing_*
+    def timing_enable(self, on: bool = True) -> None:
+        _check(self._lib.tbe_timing_enable(self._h, 1 if on else 0), "tbe_timing_enable")
+
+    def timing_read(self) -> List[Tuple[str, float]]:
+        n = ctypes.c_int32()
+        _check(self._lib.tbe_timing_count(self._h, ctypes.byref(n)), "tbe_timing_count")
+        out = []
+        for i in range(n.value):
+            name = ctypes.c_char_p()
+            ms = ctypes.c_float()
+            _check(self._lib.tbe_timing_read(self._h, i, ctypes.byref(name), ctypes.byref(ms)), "tbe_timing_read")
+            out.append((name.value.decode(), float(ms.value)))
+        return out

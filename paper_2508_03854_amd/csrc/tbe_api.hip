@@ -1,0 +1,284 @@
+// C ABI of libtbe355: argument checks, table metadata, workspace carving, stream plumbing, timing.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "tbe_internal.h"
+
+namespace tbe {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Workspace carve(const tbe_handle* h, int64_t N) {
+    Workspace w;
+    memset(&w, 0, sizeof(w));
+    const size_t n = (size_t)(N > 0 ? N : 1);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align256(off + bytes);
+        return at;
+    };
+    w.keys[0] = take(4 * n);
+    w.keys[1] = take(4 * n);
+    w.vals[0] = take(4 * n);
+    w.vals[1] = take(4 * n);
+    w.bag_of_pos = take(4 * n);
+    w.unique_rows = take(4 * n);
+    w.seg_start = take(4 * (n + 1));
+    // radix: G blocks, each owning a contiguous slice that is a whole number of tiles
+    int64_t tiles = ((int64_t)n + kRadixTile - 1) / kRadixTile;
+    int64_t G = tiles < kRadixMaxBlocks ? tiles : kRadixMaxBlocks;
+    int64_t tiles_per_block = (tiles + G - 1) / G;
+    w.radix_chunk = tiles_per_block * kRadixTile;
+    w.radix_blocks = (int)(((int64_t)n + w.radix_chunk - 1) / w.radix_chunk);
+    w.radix_hist = take(4 * (size_t)256 * (size_t)w.radix_blocks);
+    w.bin_tot = take(4 * 256);
+    w.rle_blocks = (int)(((int64_t)n + kRleTile - 1) / kRleTile);
+    w.rle_counts = take(4 * (size_t)(w.rle_blocks + 1));
+    w.counters = take(4 * 16);
+    w.cap_long = (int64_t)n / (kSegChunk + 1) + 1;
+    w.cap_chunks = 2 * ((int64_t)n / kSegChunk) + 2;
+    w.long_list = take(4 * 3 * (size_t)w.cap_long);
+    w.chunk_desc = take(4 * 2 * (size_t)w.cap_chunks);
+    w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);
+    w.total = off;
+    return w;
+}
+
+LaunchTimer::LaunchTimer(const tbe_handle* h_, hipStream_t s_, const char* name) : h(const_cast<tbe_handle*>(h_)), s(s_) {
+    if (!h->timing) return;
+    if (h->n_used == (int)h->slots.size()) {
+        TimingSlot t;
+        t.name = name;
+        if (hipEventCreate(&t.beg) != hipSuccess || hipEventCreate(&t.end) != hipSuccess) return;
+        h->slots.push_back(t);
+    }
+    slot = h->n_used++;
+    h->slots[slot].name = name;
+    (void)hipEventRecord(h->slots[slot].beg, s);
+}
+
+void LaunchTimer::done() {
+    if (slot >= 0) (void)hipEventRecord(h->slots[slot].end, s);
+}
+
+static int bits_for(uint64_t v) {  // number of bits needed to represent v (>= 1)
+    int b = 1;
+    while ((v >> b) != 0) ++b;
+    return b;
+}
+
+}  // namespace tbe
+
+using namespace tbe;
+
+extern "C" {
+
+const char* tbe_status_string(tbe_status s) {
+    switch (s) {
+        case TBE_OK: return "ok";
+        case TBE_EINVAL: return "invalid argument";
+        case TBE_ESHAPE: return "size outside the supported limits";
+        case TBE_EDTYPE: return "unknown dtype or pooling mode";
+        case TBE_EWORKSPACE: return "workspace too small";
+        case TBE_EINDEX: return "an id outside its table was seen";
+        case TBE_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtype weight_dtype, tbe_handle** out) {
+    if (!out) return TBE_EINVAL;
+    *out = nullptr;
+    if (!rows || !D) return TBE_EINVAL;
+    if (weight_dtype != TBE_F32 && weight_dtype != TBE_F16) return TBE_EDTYPE;
+    if (T < 1 || T > (1 << 20)) return TBE_ESHAPE;
+    const int dmul = weight_dtype == TBE_F16 ? 8 : 4;
+    tbe_handle* h = new (std::nothrow) tbe_handle;
+    if (!h) return TBE_EHIP;
+    h->T = T;
+    h->dtype = weight_dtype;
+    h->rows.assign(rows, rows + T);
+    h->D.assign(D, D + T);
+    h->row_base.assign(T + 1, 0);
+    h->w_off.assign(T + 1, 0);
+    h->D_off.assign(T + 1, 0);
+    int64_t sumD = 0;
+    for (int t = 0; t < T; ++t) {
+        if (rows[t] < 1 || rows[t] >= ((int64_t)1 << 31) || D[t] < 4 || D[t] > 1024 || D[t] % dmul != 0) {
+            delete h;
+            return TBE_ESHAPE;
+        }
+        h->row_base[t + 1] = h->row_base[t] + rows[t];
+        h->w_off[t + 1] = h->w_off[t] + rows[t] * (int64_t)D[t];
+        sumD += D[t];
+        h->D_off[t + 1] = (int32_t)sumD;
+        if (D[t] > h->maxD) h->maxD = D[t];
+        if (h->row_base[t + 1] >= (int64_t)0xFFFFFFFFll || sumD > (int64_t)0x7FFFFFF0ll) {
+            delete h;
+            return TBE_ESHAPE;
+        }
+    }
+    h->total_rows = h->row_base[T];
+    h->total_elems = h->w_off[T];
+    h->sumD = (int32_t)sumD;
+    h->key_bits = bits_for((uint64_t)h->total_rows);
+    if (hipGetDevice(&h->device) != hipSuccess) {
+        delete h;
+        return TBE_EHIP;
+    }
+    const size_t b_doff = align256(4 * (size_t)(T + 1)), b_rb = align256(8 * (size_t)(T + 1)), b_wo = b_rb;
+    const size_t total = b_doff + b_rb + b_wo + 256;
+    if (hipMalloc(&h->d_meta, total) != hipSuccess) {
+        delete h;
+        return TBE_EHIP;
+    }
+    char* base = static_cast<char*>(h->d_meta);
+    h->d_D_off = reinterpret_cast<int32_t*>(base);
+    h->d_row_base = reinterpret_cast<int64_t*>(base + b_doff);
+    h->d_w_off = reinterpret_cast<int64_t*>(base + b_doff + b_rb);
+    h->d_err = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo);
+    bool ok = hipMemset(h->d_meta, 0, total) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_D_off, h->D_off.data(), 4 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_row_base, h->row_base.data(), 8 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_w_off, h->w_off.data(), 8 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+        (void)hipFree(h->d_meta);
+        delete h;
+        return TBE_EHIP;
+    }
+    *out = h;
+    return TBE_OK;
+}
+
+tbe_status tbe_destroy(tbe_handle* h) {
+    if (!h) return TBE_OK;
+    for (auto& t : h->slots) {
+        (void)hipEventDestroy(t.beg);
+        (void)hipEventDestroy(t.end);
+    }
+    if (h->d_meta) (void)hipFree(h->d_meta);
+    delete h;
+    return TBE_OK;
+}
+
+static tbe_status check_batch(const tbe_handle* h, int32_t B, int64_t nnz) {
+    if (B < 1) return TBE_ESHAPE;
+    if (nnz < 0 || nnz >= (int64_t)0xFFFFFFFFll) return TBE_ESHAPE;
+    if ((int64_t)h->T * B >= ((int64_t)1 << 31)) return TBE_ESHAPE;
+    return TBE_OK;
+}
+
+tbe_status tbe_workspace_bytes(const tbe_handle* h, int32_t B, int64_t max_nnz, size_t* bytes) {
+    if (!h || !bytes) return TBE_EINVAL;
+    const tbe_status st = check_batch(h, B, max_nnz);
+    if (st != TBE_OK) return st;
+    *bytes = carve(h, max_nnz).total;
+    return TBE_OK;
+}
+
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const int64_t* indices,
+                       const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
+                       void* hip_stream) {
+    if (!h || !tables || !offsets || !out || (!indices && nnz > 0)) return TBE_EINVAL;
+    if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
+    const tbe_status st = check_batch(h, B, nnz);
+    if (st != TBE_OK) return st;
+    if (!aligned(tables, 16) || !aligned(out, 16) || !aligned(indices, 8) || !aligned(offsets, 8)) return TBE_EINVAL;
+    const hipError_t e = launch_forward(h, tables, D_offsets ? D_offsets : h->d_D_off, indices, offsets, B, nnz, pooling,
+                                        out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
+                                        const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
+                                        float eps, float momentum_scale, void* tables, float* state, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+    if (!h || !grad_out || !offsets || !tables || !state || (!indices && nnz > 0)) return TBE_EINVAL;
+    if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
+    if (!isfinite(lr) || !isfinite(eps) || eps < 0.f || !isfinite(momentum_scale) || !(momentum_scale > 0.f))
+        return TBE_EINVAL;
+    const tbe_status st = check_batch(h, B, nnz);
+    if (st != TBE_OK) return st;
+    if (!aligned(tables, 16) || !aligned(grad_out, 16) || !aligned(state, 4) || !aligned(indices, 8) ||
+        !aligned(offsets, 8))
+        return TBE_EINVAL;
+    if (nnz == 0) return TBE_OK;  // no id appears in the batch: no row has a gradient
+    if (!workspace || !aligned(workspace, 256)) return TBE_EINVAL;
+    const Workspace w = carve(h, nnz);
+    if (workspace_bytes < w.total) return TBE_EWORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = launch_linearize(h, indices, offsets, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
+                                    reinterpret_cast<uint32_t*>(ws + w.vals[0]),
+                                    reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
+    if (e != hipSuccess) return TBE_EHIP;
+    int buf = 0;
+    e = launch_radix_sort(h, w, ws, nnz, &buf, s);
+    if (e != hipSuccess) return TBE_EHIP;
+    const uint32_t* ks = reinterpret_cast<const uint32_t*>(ws + w.keys[buf]);
+    const uint32_t* vs = reinterpret_cast<const uint32_t*>(ws + w.vals[buf]);
+    e = launch_run_lengths(h, w, ws, ks, nnz, s);
+    if (e != hipSuccess) return TBE_EHIP;
+    e = launch_segment_update(h, w, ws, ks, vs, grad_out, offsets, B, nnz, pooling, lr, eps, momentum_scale, tables,
+                              state, s);
+    return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int64_t nnz, const uint32_t** keys_sorted,
+                            const uint32_t** vals_sorted, const uint32_t** unique_rows, const uint32_t** seg_start,
+                            const uint32_t** num_unique) {
+    if (!h || !workspace) return TBE_EINVAL;
+    const tbe_status st = check_batch(h, B, nnz);
+    if (st != TBE_OK) return st;
+    const Workspace w = carve(h, nnz);
+    const int passes = (h->key_bits + 7) / 8;
+    const int buf = passes & 1;  // every pass flips the double buffer, starting from 0
+    char* ws = static_cast<char*>(workspace);
+    if (keys_sorted) *keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[buf]);
+    if (vals_sorted) *vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[buf]);
+    if (unique_rows) *unique_rows = reinterpret_cast<const uint32_t*>(ws + w.unique_rows);
+    if (seg_start) *seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
+    if (num_unique) *num_unique = reinterpret_cast<const uint32_t*>(ws + w.counters);
+    return TBE_OK;
+}
+
+tbe_status tbe_poll_index_error(tbe_handle* h) {
+    if (!h) return TBE_EINVAL;
+    int32_t flag = 0;
+    if (hipDeviceSynchronize() != hipSuccess) return TBE_EHIP;
+    if (hipMemcpy(&flag, h->d_err, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return TBE_EHIP;
+    if (flag) {
+        if (hipMemset(h->d_err, 0, sizeof(flag)) != hipSuccess) return TBE_EHIP;
+        return TBE_EINDEX;
+    }
+    return TBE_OK;
+}
+
+tbe_status tbe_timing_enable(tbe_handle* h, int enable) {
+    if (!h) return TBE_EINVAL;
+    h->timing = enable != 0;
+    h->n_used = 0;
+    return TBE_OK;
+}
+
+tbe_status tbe_timing_count(tbe_handle* h, int32_t* n) {
+    if (!h || !n) return TBE_EINVAL;
+    *n = h->n_used;
+    return TBE_OK;
+}
+
+tbe_status tbe_timing_read(tbe_handle* h, int32_t i, const char** name, float* ms) {
+    if (!h || !name || !ms || i < 0 || i >= h->n_used) return TBE_EINVAL;
+    TimingSlot& t = h->slots[i];
+    if (hipEventSynchronize(t.end) != hipSuccess) return TBE_EHIP;
+    if (hipEventElapsedTime(ms, t.beg, t.end) != hipSuccess) return TBE_EHIP;
+    *name = t.name;
+    return TBE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Device-side helpers for gfx950 (64-lane wavefronts).
+#pragma once
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tbe {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() {
+    return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+__device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+
+// smallest power of two >= x, for 1 <= x <= 64
+__device__ __forceinline__ int pow2ceil64(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+    const int l = lane_id();
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        uint32_t n = __shfl_up(v, o, kWave);
+        if (l >= o) v += n;
+    }
+    return v;
+}
+
+// Exclusive prefix sum across a block of NT threads (NT multiple of 64). smem: NT/64 words.
+// Returns the exclusive prefix of this thread; *total is the block sum (same in every thread).
+template <int NT>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* smem, uint32_t* total) {
+    const int l = lane_id();
+    const int w = threadIdx.x >> 6;
+    const uint32_t inc = wave_incl_scan(v);
+    if (l == kWave - 1) smem[w] = inc;
+    __syncthreads();
+    uint32_t wbase = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NT / kWave; ++i) {
+        const uint32_t s = smem[i];
+        if (i < w) wbase += s;
+        tot += s;
+    }
+    __syncthreads();  // smem may be reused by the caller after this
+    *total = tot;
+    return wbase + inc - v;
+}
+
+// ---- 16-byte row fragments ---------------------------------------------------------------------
+// RowIO<WT>::kVec elements of a table row travel in one 16-byte load.
+template <typename WT>
+struct RowIO;
+
+template <>
+struct RowIO<float> {
+    static constexpr int kVec = 4;
+    static __device__ __forceinline__ void load(const float* p, float (&x)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
+    // 4-element fragment used by the optimizer step (one lane owns 4 columns)
+    static __device__ __forceinline__ void load4(const float* p, float (&x)[4]) { load(p, x); }
+    static __device__ __forceinline__ void store4(float* p, const float (&x)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    }
+};
+
+template <>
+struct RowIO<__half> {
+    static constexpr int kVec = 8;
+    static __device__ __forceinline__ void load(const __half* p, float (&x)[8]) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xFFFFu)));
+            x[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+        }
+    }
+    static __device__ __forceinline__ void load4(const __half* p, float (&x)[4]) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(p);
+        x[0] = __half2float(__ushort_as_half((unsigned short)(raw.x & 0xFFFFu)));
+        x[1] = __half2float(__ushort_as_half((unsigned short)(raw.x >> 16)));
+        x[2] = __half2float(__ushort_as_half((unsigned short)(raw.y & 0xFFFFu)));
+        x[3] = __half2float(__ushort_as_half((unsigned short)(raw.y >> 16)));
+    }
+    // one rounding, to nearest even, from the fp32 result to the stored binary16
+    static __device__ __forceinline__ void store4(__half* p, const float (&x)[4]) {
+        uint2 raw;
+        raw.x = (uint32_t)__half_as_ushort(__float2half_rn(x[0])) | ((uint32_t)__half_as_ushort(__float2half_rn(x[1])) << 16);
+        raw.y = (uint32_t)__half_as_ushort(__float2half_rn(x[2])) | ((uint32_t)__half_as_ushort(__float2half_rn(x[3])) << 16);
+        *reinterpret_cast<uint2*>(p) = raw;
+    }
+};
+
+}  // namespace tbe

@@ -1,0 +1,163 @@
+// Forward: pooled lookup, one wavefront per bag.
+//
+// A bag's rows are D_t * sizeof(weight) contiguous bytes each (128 B .. 1 KB for the shapes of interest),
+// so a 64-lane wavefront would waste most lanes on one row.  The wavefront is therefore split into
+// G = 64 / LPR groups of LPR lanes, LPR = D_t / kVec lanes covering one row with one 16-byte load per
+// lane; the groups walk the bag in an interleaved fashion, four rows per group in flight, and a
+// butterfly over the groups folds the partial sums at the end.  The bag's ids are read with one
+// coalesced 64-wide load and handed to the groups with cross-lane reads.
+#include "tbe_device.cuh"
+#include "tbe_internal.h"
+
+namespace tbe {
+
+constexpr int kFwdThreads = 256;
+constexpr int kFwdUnroll = 4;
+
+template <typename WT, int NC, bool MEAN>
+__device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const int D, const int64_t R,
+                                            const int64_t* __restrict__ indices, const int64_t start,
+                                            const int64_t end, float* __restrict__ out_row, int32_t* err) {
+    constexpr int V = RowIO<WT>::kVec;
+    const int lane = lane_id();
+    const int nl = (D + V - 1) / V;  // lanes needed by one row
+    const int LPR = nl >= kWave ? kWave : pow2ceil64(nl);
+    const int G = kWave / LPR;
+    const int sub = lane / LPR;
+    const int lc = (lane & (LPR - 1)) * V;
+
+    float acc[NC][V];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[c][v] = 0.f;
+
+    for (int64_t base = start; base < end; base += kWave) {
+        const int n = (int)((end - base) < (int64_t)kWave ? (end - base) : (int64_t)kWave);
+        int32_t my = -1;
+        if (lane < n) {
+            const int64_t id = indices[base + lane];
+            if (id >= 0 && id < R) my = (int32_t)id;
+            else atomicOr(err, 1);
+        }
+        for (int k0 = 0; k0 < n; k0 += kFwdUnroll * G) {
+            int32_t id[kFwdUnroll];
+#pragma unroll
+            for (int u = 0; u < kFwdUnroll; ++u) {
+                const int k = k0 + u * G + sub;
+                const int32_t got = __shfl(my, k & (kWave - 1), kWave);
+                id[u] = (k < n) ? got : -1;
+            }
+            float x[kFwdUnroll][NC][V];
+#pragma unroll
+            for (int u = 0; u < kFwdUnroll; ++u) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const int col = lc + c * kWave * V;
+                    if (id[u] >= 0 && col < D) {
+                        RowIO<WT>::load(table + (int64_t)id[u] * D + col, x[u][c]);
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < V; ++v) x[u][c][v] = 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kFwdUnroll; ++u)
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[c][v] += x[u][c][v];
+        }
+    }
+    // fold the groups
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[c][v] += __shfl_xor(acc[c][v], o, kWave);
+    }
+    float scale = 1.f;
+    if (MEAN) {
+        const int64_t L = end - start;
+        scale = L > 0 ? 1.f / (float)L : 0.f;
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int col = lc + c * kWave * V;
+            if (col < D) {
+#pragma unroll
+                for (int v4 = 0; v4 < V; v4 += 4) {
+                    *reinterpret_cast<float4*>(out_row + col + v4) =
+                        make_float4(acc[c][v4] * scale, acc[c][v4 + 1] * scale, acc[c][v4 + 2] * scale,
+                                    acc[c][v4 + 3] * scale);
+                }
+            }
+        }
+    }
+}
+
+template <typename WT, bool MEAN>
+__global__ __launch_bounds__(kFwdThreads) void forward_kernel(const WT* __restrict__ weights,
+                                                              const int64_t* __restrict__ indices,
+                                                              const int64_t* __restrict__ offsets,
+                                                              const int32_t* __restrict__ D_off,
+                                                              const int64_t* __restrict__ w_off,
+                                                              const int64_t* __restrict__ row_base, const int32_t B,
+                                                              const int64_t nbags, const int64_t nnz,
+                                                              const int32_t sumD,
+                                                              float* __restrict__ out, int32_t* err) {
+    constexpr int V = RowIO<WT>::kVec;
+    const int64_t bag = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
+    if (bag >= nbags) return;
+    const int32_t t = (int32_t)(bag / B);
+    const int32_t b = (int32_t)(bag - (int64_t)t * B);
+    const int32_t d0 = D_off[t];
+    const int D = D_off[t + 1] - d0;
+    const int64_t R = row_base[t + 1] - row_base[t];
+    // clamped so that a malformed offsets array can never take a read outside indices[0, nnz)
+    int64_t start = offsets[bag];
+    int64_t end = offsets[bag + 1];
+    start = start < 0 ? 0 : (start > nnz ? nnz : start);
+    end = end < start ? start : (end > nnz ? nnz : end);
+    const WT* table = weights + w_off[t];
+    float* out_row = out + (int64_t)b * sumD + d0;
+    if (D <= kWave * V)
+        forward_bag<WT, 1, MEAN>(table, D, R, indices, start, end, out_row, err);
+    else if (D <= 2 * kWave * V)
+        forward_bag<WT, 2, MEAN>(table, D, R, indices, start, end, out_row, err);
+    else
+        forward_bag<WT, 4, MEAN>(table, D, R, indices, start, end, out_row, err);
+}
+
+hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
+                          const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out, hipStream_t s) {
+    const int64_t nbags = (int64_t)h->T * B;
+    if (nbags == 0) return hipSuccess;
+    const int wpb = kFwdThreads / kWave;
+    const dim3 grid((unsigned)((nbags + wpb - 1) / wpb)), block(kFwdThreads);
+    LaunchTimer tm(h, s, "forward_pool");
+    const bool mean = pooling == TBE_MEAN;
+    if (h->dtype == TBE_F32) {
+        const float* w = static_cast<const float*>(tables);
+        if (mean)
+            forward_kernel<float, true><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, B,
+                                                               nbags, nnz, h->sumD, out, h->d_err);
+        else
+            forward_kernel<float, false><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
+                                                                B, nbags, nnz, h->sumD, out, h->d_err);
+    } else {
+        const __half* w = static_cast<const __half*>(tables);
+        if (mean)
+            forward_kernel<__half, true><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
+                                                                B, nbags, nnz, h->sumD, out, h->d_err);
+        else
+            forward_kernel<__half, false><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
+                                                                 h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
+    }
+    tm.done();
+    return hipGetLastError();
+}
+
+}  // namespace tbe

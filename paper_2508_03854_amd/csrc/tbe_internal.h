@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of libtbe355 (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "tbe355.h"
+
+namespace tbe {
+
+// ---- tunables that fix the workspace layout -------------------------------------------------
+constexpr int kSegChunk = 512;         // a unique row with more lookups than this is split into chunks of this size
+constexpr int kRadixTile = 2048;       // elements per radix-sort tile (256 threads x 8)
+constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous slice of the input
+constexpr int kRleTile = 2048;         // elements per run-length tile
+constexpr int kLinTile = 2048;         // positions per linearize tile
+
+struct TimingSlot {
+    const char* name;
+    hipEvent_t beg, end;
+};
+
+}  // namespace tbe
+
+struct tbe_handle {
+    int32_t T = 0;
+    tbe_dtype dtype = TBE_F32;
+    int device = 0;
+    int64_t total_rows = 0;
+    int64_t total_elems = 0;
+    int32_t sumD = 0;
+    int32_t maxD = 0;
+    int key_bits = 1;  // bits needed to hold the value total_rows (the key given to invalid ids)
+    std::vector<int64_t> rows, row_base, w_off;
+    std::vector<int32_t> D, D_off;
+    // device metadata, one allocation
+    void* d_meta = nullptr;
+    int32_t* d_D_off = nullptr;     // [T+1]
+    int64_t* d_row_base = nullptr;  // [T+1]
+    int64_t* d_w_off = nullptr;     // [T+1]
+    int32_t* d_err = nullptr;       // sticky invalid-id flag
+    // timing
+    bool timing = false;
+    std::vector<tbe::TimingSlot> slots;  // pool of event pairs
+    int n_used = 0;                      // slots used by the calls since timing was (re)enabled
+};
+
+namespace tbe {
+
+// Workspace carving for a batch of N lookups (all offsets in bytes, 256-byte aligned).
+struct Workspace {
+    size_t keys[2], vals[2], bag_of_pos, unique_rows, seg_start, radix_hist, bin_tot, rle_counts, counters, long_list,
+        chunk_desc, partial, total;
+    int radix_blocks;     // G
+    int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
+    int rle_blocks;
+    int64_t cap_long, cap_chunks;
+};
+Workspace carve(const tbe_handle* h, int64_t N);
+
+// RAII-free helper: brackets one kernel launch with events when timing is on.
+struct LaunchTimer {
+    tbe_handle* h;
+    hipStream_t s;
+    int slot = -1;
+    LaunchTimer(const tbe_handle* h_, hipStream_t s_, const char* name);
+    void done();
+};
+
+// launchers (each returns hipGetLastError() after its launches)
+hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
+                          const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
+                          hipStream_t s);
+hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
+                            uint32_t* keys, uint32_t* vals, uint32_t* bag_of_pos, hipStream_t s);
+// sorts (keys[0], vals[0]) of the workspace; returns in *result_buf which buffer (0/1) holds the result
+hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted, int64_t N,
+                              hipStream_t s);
+hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted,
+                                 const uint32_t* vals_sorted, const float* grad_out, const int64_t* offsets, int32_t B,
+                                 int64_t N, tbe_pooling pooling, float lr, float eps, float c, void* tables, float* state,
+                                 hipStream_t s);
+
+}  // namespace tbe

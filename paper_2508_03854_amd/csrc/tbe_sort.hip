@@ -1,0 +1,403 @@
+// Integer half of the backward pass: linearise ids into row keys, stable LSD radix sort of (key, position),
+// run-length segmentation into unique rows.  Everything here is exact integer work.
+#include "tbe_device.cuh"
+#include "tbe_internal.h"
+
+namespace tbe {
+
+// =================================================================================================
+// linearize: key[p] = row_base[t(p)] + indices[p], val[p] = p, bag_of_pos[p] = linear bag id of p
+// =================================================================================================
+constexpr int kLinThreads = 256;
+
+// first i in [lo, hi] with a[i] > x   (caller guarantees a[hi] > x)
+__device__ __forceinline__ int64_t upper_bound_i64(const int64_t* __restrict__ a, int64_t lo, int64_t hi, int64_t x) {
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] > x) hi = mid;
+        else lo = mid + 1;
+    }
+    return lo;
+}
+
+// A block owns kLinTile consecutive positions.  It finds the bags that own its first and last position
+// with two binary searches in the global offsets, stages that offsets segment in LDS (relative to the
+// tile start), and every thread then finds the bag of its position with a short search in LDS.
+__global__ __launch_bounds__(kLinThreads) void linearize_kernel(const int64_t* __restrict__ indices,
+                                                                const int64_t* __restrict__ offsets,
+                                                                const int64_t nbags, const int32_t B,
+                                                                const int64_t* __restrict__ row_base,
+                                                                const uint32_t invalid_key, const int64_t N,
+                                                                uint32_t* __restrict__ keys, uint32_t* __restrict__ vals,
+                                                                uint32_t* __restrict__ bag_of_pos, int32_t* err) {
+    __shared__ int32_t s_off[kLinTile + 2];
+    __shared__ int64_t s_lo, s_hi;
+    const int64_t p0 = (int64_t)blockIdx.x * kLinTile;
+    const int64_t p1 = (p0 + kLinTile < N) ? p0 + kLinTile : N;
+    if (p0 >= N) return;
+    if (threadIdx.x == 0) {
+        // owner of p: the bag with offsets[bag] <= p < offsets[bag+1]  ==  (first i with offsets[i] > p) - 1.
+        // Searching i in [0, nbags] and clamping keeps every later access in range even for malformed offsets.
+        int64_t lo = upper_bound_i64(offsets, 0, nbags, p0) - 1;
+        int64_t hi = upper_bound_i64(offsets, 0, nbags, p1 - 1) - 1;
+        lo = lo < 0 ? 0 : (lo > nbags - 1 ? nbags - 1 : lo);
+        hi = hi < lo ? lo : (hi > nbags - 1 ? nbags - 1 : hi);
+        s_lo = lo;
+        s_hi = hi;
+    }
+    __syncthreads();
+    const int64_t lo = s_lo, hi = s_hi;
+    const int64_t nb = hi - lo + 1;             // bags touched by this tile (>= 1)
+    const bool staged = nb + 1 <= kLinTile + 2;  // nb+1 offsets entries fit in LDS
+    if (staged) {
+        for (int i = threadIdx.x; i <= (int)nb; i += kLinThreads) {
+            int64_t rel = offsets[lo + i] - p0;
+            rel = rel < -1 ? -1 : (rel > kLinTile ? kLinTile : rel);
+            s_off[i] = (int32_t)rel;
+        }
+    }
+    __syncthreads();
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += kLinThreads) {
+        int64_t bag;
+        if (staged) {
+            const int32_t rel = (int32_t)(p - p0);
+            int a = 0, b = (int)nb;  // first i in [0, nb] with s_off[i] > rel; s_off[nb] > rel for well-formed input
+            while (a < b) {
+                const int mid = (a + b) >> 1;
+                if (s_off[mid] > rel) b = mid;
+                else a = mid + 1;
+            }
+            bag = lo + a - 1;
+        } else {  // a tile that spans more than kLinTile bags (long runs of empty bags): search in global memory
+            bag = upper_bound_i64(offsets, lo, hi + 1, p) - 1;
+        }
+        bag = bag < lo ? lo : (bag > hi ? hi : bag);
+        const int32_t t = (int32_t)(bag / B);
+        const int64_t rb = row_base[t];
+        const int64_t R = row_base[t + 1] - rb;
+        const int64_t id = indices[p];
+        uint32_t key;
+        if (id >= 0 && id < R) {
+            key = (uint32_t)(rb + id);
+        } else {
+            key = invalid_key;
+            atomicOr(err, 1);
+        }
+        keys[p] = key;
+        vals[p] = (uint32_t)p;
+        bag_of_pos[p] = (uint32_t)bag;
+    }
+}
+
+hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
+                            uint32_t* keys, uint32_t* vals, uint32_t* bag_of_pos, hipStream_t s) {
+    const int64_t nbags = (int64_t)h->T * B;
+    const unsigned grid = (unsigned)((N + kLinTile - 1) / kLinTile);
+    LaunchTimer tm(h, s, "linearize");
+    linearize_kernel<<<grid, kLinThreads, 0, s>>>(indices, offsets, nbags, B, h->d_row_base, (uint32_t)h->total_rows, N,
+                                                  keys, vals, bag_of_pos, h->d_err);
+    tm.done();
+    return hipGetLastError();
+}
+
+// =================================================================================================
+// LSD radix sort, <= 8 bits per pass, 3 kernels per pass:
+//   hist    : block k counts the digits of its contiguous slice          -> ghist[digit][k]
+//   binscan : block d turns ghist[d][*] into an exclusive scan in place   -> bin_tot[d]
+//   scatter : block k ranks its slice tile by tile and writes (key, val) to its final place
+// Block k's slice precedes block k+1's, and the scatter ranks elements in input order, so the sort is stable.
+// =================================================================================================
+constexpr int kRsThreads = 256;
+constexpr int kRsWaves = kRsThreads / kWave;
+constexpr int kRsItems = kRadixTile / kRsThreads;  // 8
+constexpr int kRsBins = 256;
+
+__global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* __restrict__ keys, const int64_t N,
+                                                                const int64_t chunk, const int shift,
+                                                                const uint32_t mask, const int nbins, const int G,
+                                                                uint32_t* __restrict__ ghist) {
+    __shared__ uint32_t h[kRsWaves][kRsBins];
+    for (int i = threadIdx.x; i < kRsWaves * kRsBins; i += kRsThreads) (&h[0][0])[i] = 0u;
+    __syncthreads();
+    const int w = threadIdx.x >> 6;
+    const int64_t s = (int64_t)blockIdx.x * chunk;
+    const int64_t e = (s + chunk < N) ? s + chunk : N;
+    for (int64_t i = s + threadIdx.x; i < e; i += kRsThreads) {
+        const uint32_t d = (keys[i] >> shift) & mask;
+        atomicAdd(&h[w][d], 1u);
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < nbins; d += kRsThreads) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int ww = 0; ww < kRsWaves; ++ww) c += h[ww][d];
+        ghist[(size_t)d * G + blockIdx.x] = c;
+    }
+}
+
+// grid = nbins blocks; block d scans its G counts in place (exclusive) and writes the digit total
+__global__ __launch_bounds__(kRsThreads) void radix_binscan_kernel(uint32_t* __restrict__ ghist, const int G,
+                                                                   uint32_t* __restrict__ bin_tot) {
+    __shared__ uint32_t smem[kRsWaves];
+    uint32_t* row = ghist + (size_t)blockIdx.x * G;
+    uint32_t carry = 0;
+    for (int base = 0; base < G; base += kRsThreads) {
+        const int i = base + threadIdx.x;
+        const uint32_t v = (i < G) ? row[i] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<kRsThreads>(v, smem, &tot);
+        if (i < G) row[i] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) bin_tot[blockIdx.x] = carry;
+}
+
+__global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in,
+                                                                   const uint32_t* __restrict__ vals_in,
+                                                                   uint32_t* __restrict__ keys_out,
+                                                                   uint32_t* __restrict__ vals_out, const int64_t N,
+                                                                   const int64_t chunk, const int shift,
+                                                                   const uint32_t mask, const int nbins, const int G,
+                                                                   const uint32_t* __restrict__ ghist,
+                                                                   const uint32_t* __restrict__ bin_tot) {
+    __shared__ uint32_t s_cnt[kRsWaves][kRsBins];  // per-wave digit counts, then per-wave exclusive offsets
+    __shared__ uint32_t s_base[kRsBins];           // where this block's next element of digit d goes
+    __shared__ uint32_t s_dstart[kRsBins];         // start of digit d inside the locally sorted tile
+    __shared__ uint32_t s_keys[kRadixTile];
+    __shared__ uint32_t s_vals[kRadixTile];
+    __shared__ uint32_t s_scan[kRsWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = lane_id();
+    const int w = tid >> 6;
+    const uint64_t lt = lanemask_lt();
+
+    {   // global base of every digit for this block: (digits below d, all blocks) + (digit d, blocks before this one)
+        const uint32_t t = (tid < nbins) ? bin_tot[tid] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<kRsThreads>(t, s_scan, &tot);
+        s_base[tid] = (tid < nbins) ? ex + ghist[(size_t)tid * G + blockIdx.x] : 0u;
+    }
+    const int64_t s = (int64_t)blockIdx.x * chunk;
+    const int64_t e = (s + chunk < N) ? s + chunk : N;
+
+    for (int64_t tile = s; tile < e; tile += kRadixTile) {
+        for (int i = tid; i < kRsWaves * kRsBins; i += kRsThreads) (&s_cnt[0][0])[i] = 0u;
+        __syncthreads();  // also orders the s_base update / s_keys reads of the previous tile
+
+        uint32_t key[kRsItems], val[kRsItems], off[kRsItems];
+        const int64_t wbase = tile + (int64_t)w * (kWave * kRsItems);
+#pragma unroll
+        for (int k = 0; k < kRsItems; ++k) {
+            const int64_t i = wbase + k * kWave + lane;
+            const bool valid = i < e;
+            key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
+            val[k] = valid ? vals_in[i] : 0u;
+        }
+        // rank inside the wave, item by item in input order: peers = valid lanes holding the same digit
+#pragma unroll
+        for (int k = 0; k < kRsItems; ++k) {
+            const int64_t i = wbase + k * kWave + lane;
+            const bool valid = i < e;
+            const uint32_t d = (key[k] >> shift) & mask;
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (d >> b) & 1u;
+                const uint64_t m = __ballot(valid && bit);
+                peers &= bit ? m : ~m;
+            }
+            uint32_t old = 0;
+            const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : 0;
+            if (valid && lane == leader) old = atomicAdd(&s_cnt[w][d], (uint32_t)__popcll(peers));
+            old = __shfl(old, leader, kWave);
+            off[k] = old + (uint32_t)__popcll(peers & lt);
+        }
+        __syncthreads();
+        // per digit: exclusive offsets over the waves, tile total, exclusive scan over the digits
+        uint32_t my_tot = 0;
+        {
+            uint32_t run = 0;
+#pragma unroll
+            for (int ww = 0; ww < kRsWaves; ++ww) {
+                const uint32_t c = s_cnt[ww][tid];
+                s_cnt[ww][tid] = run;
+                run += c;
+            }
+            my_tot = run;
+            uint32_t tot;
+            const uint32_t ex = block_excl_scan<kRsThreads>(my_tot, s_scan, &tot);
+            s_dstart[tid] = ex;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kRsItems; ++k) {
+            const int64_t i = wbase + k * kWave + lane;
+            if (i < e) {
+                const uint32_t d = (key[k] >> shift) & mask;
+                const uint32_t pos = s_dstart[d] + s_cnt[w][d] + off[k];
+                s_keys[pos] = key[k];
+                s_vals[pos] = val[k];
+            }
+        }
+        __syncthreads();
+        const int cnt = (int)((e - tile) < (int64_t)kRadixTile ? (e - tile) : (int64_t)kRadixTile);
+        for (int j = tid; j < cnt; j += kRsThreads) {
+            const uint32_t kk = s_keys[j];
+            const uint32_t d = (kk >> shift) & mask;
+            const uint32_t dst = s_base[d] + ((uint32_t)j - s_dstart[d]);
+            keys_out[dst] = kk;
+            vals_out[dst] = s_vals[j];
+        }
+        __syncthreads();
+        s_base[tid] += my_tot;
+    }
+}
+
+hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf,
+                             hipStream_t s) {
+    const int passes = (h->key_bits + 7) / 8;
+    const int bits = (h->key_bits + passes - 1) / passes;  // <= 8
+    const int nbins = 1 << bits;
+    const uint32_t mask = (uint32_t)nbins - 1u;
+    const int G = w.radix_blocks;
+    uint32_t* ghist = reinterpret_cast<uint32_t*>(ws + w.radix_hist);
+    uint32_t* bin_tot = reinterpret_cast<uint32_t*>(ws + w.bin_tot);
+    int cur = 0;
+    for (int p = 0; p < passes; ++p) {
+        const uint32_t* kin = reinterpret_cast<const uint32_t*>(ws + w.keys[cur]);
+        const uint32_t* vin = reinterpret_cast<const uint32_t*>(ws + w.vals[cur]);
+        uint32_t* kout = reinterpret_cast<uint32_t*>(ws + w.keys[cur ^ 1]);
+        uint32_t* vout = reinterpret_cast<uint32_t*>(ws + w.vals[cur ^ 1]);
+        const int shift = p * bits;
+        {
+            LaunchTimer tm(h, s, "radix_hist");
+            radix_hist_kernel<<<G, kRsThreads, 0, s>>>(kin, N, w.radix_chunk, shift, mask, nbins, G, ghist);
+            tm.done();
+        }
+        {
+            LaunchTimer tm(h, s, "radix_binscan");
+            radix_binscan_kernel<<<nbins, kRsThreads, 0, s>>>(ghist, G, bin_tot);
+            tm.done();
+        }
+        {
+            LaunchTimer tm(h, s, "radix_scatter");
+            radix_scatter_kernel<<<G, kRsThreads, 0, s>>>(kin, vin, kout, vout, N, w.radix_chunk, shift, mask, nbins, G,
+                                                          ghist, bin_tot);
+            tm.done();
+        }
+        cur ^= 1;
+    }
+    *result_buf = cur;
+    return hipGetLastError();
+}
+
+// =================================================================================================
+// run-length segmentation of the sorted keys: unique_rows, seg_start, num_unique
+// Element order inside a tile: 8 rows of 256, row k / wave w / lane l is element k*256 + w*64 + l, so
+// every (k, w) pair is a run of 64 consecutive elements and ballots give exact ranks.
+// =================================================================================================
+constexpr int kRleThreads = 256;
+constexpr int kRleItems = kRleTile / kRleThreads;            // 8
+constexpr int kRleRuns = kRleItems * (kRleThreads / kWave);  // 32 runs of 64 elements
+
+__device__ __forceinline__ bool is_head(const uint32_t* __restrict__ keys, int64_t i, int64_t N) {
+    if (i >= N) return false;
+    if (i == 0) return true;
+    return keys[i] != keys[i - 1];
+}
+
+__global__ __launch_bounds__(kRleThreads) void rle_count_kernel(const uint32_t* __restrict__ keys, const int64_t N,
+                                                                uint32_t* __restrict__ block_counts) {
+    __shared__ uint32_t s_w[kRleThreads / kWave];
+    const int64_t base = (int64_t)blockIdx.x * kRleTile;
+    uint32_t c = 0;
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) c += is_head(keys, base + k * kRleThreads + threadIdx.x, N) ? 1u : 0u;
+    uint32_t tot;
+    (void)block_excl_scan<kRleThreads>(c, s_w, &tot);
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = tot;
+}
+
+// single block: exclusive scan of the per-tile head counts in place; writes num_unique, the closing
+// seg_start entry, and clears the counters the segment scheduler will bump.
+__global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ block_counts, const int nblocks,
+                                                        const int64_t N, uint32_t* __restrict__ seg_start,
+                                                        uint32_t* __restrict__ counters) {
+    __shared__ uint32_t smem[1024 / kWave];
+    uint32_t carry = 0;
+    for (int base = 0; base < nblocks; base += 1024) {
+        const int i = base + threadIdx.x;
+        const uint32_t v = (i < nblocks) ? block_counts[i] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<1024>(v, smem, &tot);
+        if (i < nblocks) block_counts[i] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        counters[0] = carry;  // num_unique
+        counters[1] = 0u;     // number of long rows
+        counters[2] = 0u;     // number of long-row chunks
+        seg_start[carry] = (uint32_t)N;
+    }
+}
+
+__global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys, const int64_t N,
+                                                                const uint32_t* __restrict__ block_base,
+                                                                uint32_t* __restrict__ unique_rows,
+                                                                uint32_t* __restrict__ seg_start) {
+    __shared__ uint32_t s_run[kRleRuns];
+    const int lane = lane_id();
+    const int w = threadIdx.x >> 6;
+    const uint64_t lt = lanemask_lt();
+    const int64_t base = (int64_t)blockIdx.x * kRleTile;
+    uint64_t heads[kRleItems];
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) {
+        heads[k] = __ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N));
+        if (lane == 0) s_run[k * (kRleThreads / kWave) + w] = (uint32_t)__popcll(heads[k]);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {  // one wavefront scans the 32 run counts
+        const uint32_t v = (threadIdx.x < kRleRuns) ? s_run[threadIdx.x] : 0u;
+        const uint32_t inc = wave_incl_scan(v);
+        if (threadIdx.x < kRleRuns) s_run[threadIdx.x] = inc - v;
+    }
+    __syncthreads();
+    const uint32_t bb = block_base[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) {
+        if ((heads[k] >> lane) & 1ull) {
+            const int64_t i = base + k * kRleThreads + threadIdx.x;
+            const uint32_t u = bb + s_run[k * (kRleThreads / kWave) + w] + (uint32_t)__popcll(heads[k] & lt);
+            unique_rows[u] = keys[i];
+            seg_start[u] = (uint32_t)i;
+        }
+    }
+}
+
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted, int64_t N,
+                              hipStream_t s) {
+    uint32_t* counts = reinterpret_cast<uint32_t*>(ws + w.rle_counts);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
+    uint32_t* unique_rows = reinterpret_cast<uint32_t*>(ws + w.unique_rows);
+    uint32_t* seg_start = reinterpret_cast<uint32_t*>(ws + w.seg_start);
+    {
+        LaunchTimer tm(h, s, "rle_count");
+        rle_count_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, N, counts);
+        tm.done();
+    }
+    {
+        LaunchTimer tm(h, s, "rle_scan");
+        rle_scan_kernel<<<1, 1024, 0, s>>>(counts, w.rle_blocks, N, seg_start, counters);
+        tm.done();
+    }
+    {
+        LaunchTimer tm(h, s, "rle_write");
+        rle_write_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, N, counts, unique_rows, seg_start);
+        tm.done();
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tbe

@@ -1,0 +1,146 @@
+"""Shared driver of the GPU parity tests: runs the HIP path (through the C ABI binding) and the CPU
+oracle on the same seeded inputs and compares them.  Not a test module itself."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import workloads as W
+from paper_2508_03854_amd import TBE
+
+# float tolerances of the parity bar: |gpu - ref| <= rtol*|ref| + rtol*scale, with `scale` the magnitude
+# of the operands (max |w| for weights and pooled sums): a purely relative test is ill-posed for sums
+# that cancel.  fp32 tables and moments: rtol 1e-5.  fp16 tables: rtol 1e-2, and additionally at most one
+# binary16 ulp away from the oracle's correctly rounded value.
+RTOL_F32 = 1e-5
+RTOL_F16 = 1e-2
+
+
+def host_tables(cfg: W.Config):
+    tabs = []
+    for t in range(cfg.T):
+        w = W.weight_rows(cfg, t, torch.arange(cfg.rows[t]))
+        tabs.append(w.numpy() if cfg.weight_dtype == "f32" else w.to(torch.float16).numpy())
+    return tabs
+
+
+def flat_from_tables(tabs, device="cuda"):
+    return torch.from_numpy(np.concatenate([a.reshape(-1) for a in tabs])).to(device)
+
+
+def split_flat(flat_np: np.ndarray, cfg: W.Config):
+    woff = cfg.w_offsets()
+    return [flat_np[woff[t]:woff[t + 1]].reshape(cfg.rows[t], cfg.D[t]) for t in range(cfg.T)]
+
+
+def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, scale: float, what: str):
+    got64, ref64 = got.astype(np.float64), ref.astype(np.float64)
+    err = np.abs(got64 - ref64)
+    tol = rtol * np.abs(ref64) + rtol * scale
+    bad = err > tol
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst at {i}: "
+                             f"got {got64[i]!r} ref {ref64[i]!r} err {err[i]:.3e} tol {tol[i]:.3e}")
+    return float(err.max()) if err.size else 0.0
+
+
+def half_ulp_distance(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Distance in binary16 ulps between two float16 arrays (finite values)."""
+    def ordered(x):
+        u = x.view(np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7FFF), u)
+    return np.abs(ordered(a) - ordered(b))
+
+
+def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor, tabs, state_np: np.ndarray,
+               idx: torch.Tensor, off: torch.Tensor, gout: torch.Tensor, ws: torch.Tensor, check_sorted: bool = True,
+               same_inputs: bool = True):
+    """One forward + backward on both sides, in place; compares everything.  Returns a dict of error figures.
+    same_inputs: both sides start this step from bit-identical weights (true for the first step).  After a
+    step on fp16 tables the two sides may already differ by one binary16 ulp where the fp32 and fp64 results
+    straddle a rounding boundary, so later steps are held to the fp16 tolerance only."""
+    B = cfg.B
+    idx_np, off_np, go_np = idx.numpy(), off.numpy(), gout.numpy()
+    d_idx, d_off, d_go = idx.cuda(), off.cuda(), gout.cuda()
+    w_scale = cfg.w_scale
+    report = {}
+
+    # ---- forward
+    out_ref = oracle.forward(tabs, idx_np, off_np, B, cfg.pooling)
+    out_gpu = tbe.forward(flat, d_idx, d_off, B, cfg.pooling).cpu().numpy()
+    assert not tbe.poll_index_error()
+    fwd_rtol = RTOL_F32 if (cfg.weight_dtype == "f32" or same_inputs) else RTOL_F16
+    report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, w_scale, "forward")
+
+    # ---- backward + optimizer
+    prev_tabs = split_flat(flat.cpu().numpy(), cfg)      # the GPU's own weights and moments before the step
+    prev_state = state.cpu().numpy()
+    res = oracle.backward_rowwise_adagrad(tabs, state_np, go_np, idx_np, off_np, B, cfg.pooling, cfg.lr, cfg.eps, cfg.c)
+    tbe.backward_rowwise_adagrad(d_go, d_idx, d_off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
+                                 momentum_scale=cfg.c)
+    assert not tbe.poll_index_error()
+    nnz = idx.numel()
+    if check_sorted and nnz > 0:
+        dbg = tbe.debug_sorted(ws, B, nnz)
+        assert dbg["num_unique"] == res.U, (dbg["num_unique"], res.U)
+        assert np.array_equal(dbg["keys_sorted"].numpy(), res.keys_sorted), "keys_sorted differs"
+        assert np.array_equal(dbg["vals_sorted"].numpy(), res.order), "stable order differs"
+        assert np.array_equal(dbg["unique_rows"].numpy(), res.unique_rows), "unique_rows differs"
+        assert np.array_equal(dbg["seg_start"].numpy(), res.seg_start), "seg_start differs"
+    report["U"] = res.U
+    report["max_seg"] = int(np.diff(res.seg_start).max()) if res.U else 0
+
+    flat_np = flat.cpu().numpy()
+    state_gpu = state.cpu().numpy()
+    gpu_tabs = split_flat(flat_np, cfg)
+    touched = np.zeros(cfg.total_rows, dtype=bool)
+    touched[res.unique_rows] = True
+    base = cfg.row_base()
+    # untouched rows keep their bits (weights and moments)
+    iv = np.uint32 if cfg.weight_dtype == "f32" else np.uint16
+    for t in range(cfg.T):
+        m = ~touched[base[t]:base[t + 1]]
+        assert np.array_equal(gpu_tabs[t][m].view(iv), prev_tabs[t][m].view(iv)), f"untouched rows of table {t} changed"
+    assert np.array_equal(state_gpu[~touched].view(np.uint32), prev_state[~touched].view(np.uint32))
+    # touched rows: floats within tolerance
+    werr, ulp_bad, ulp_n = 0.0, 0, 0
+    for t in range(cfg.T):
+        m = touched[base[t]:base[t + 1]]
+        if not m.any():
+            continue
+        if cfg.weight_dtype == "f32":
+            werr = max(werr, assert_close(gpu_tabs[t][m], tabs[t][m], RTOL_F32, w_scale, f"weights of table {t}"))
+        else:
+            werr = max(werr, assert_close(gpu_tabs[t][m], tabs[t][m], RTOL_F16, w_scale, f"weights of table {t}"))
+            if same_inputs:
+                d = half_ulp_distance(gpu_tabs[t][m], tabs[t][m])
+                assert d.max() <= 1, f"fp16 weights of table {t}: {int(d.max())} ulps from the oracle"
+                ulp_bad += int((d > 0).sum())
+                ulp_n += d.size
+    if ulp_n:
+        assert ulp_bad <= max(2, 2e-3 * ulp_n), f"{ulp_bad}/{ulp_n} fp16 weights round differently from the oracle"
+        report["fp16_ulp_mismatch_frac"] = ulp_bad / ulp_n
+    report["w_max_err"] = werr
+    report["v_max_err"] = assert_close(state_gpu[touched], state_np[touched], RTOL_F32, 1e-6, "moments")
+    return report
+
+
+def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_sorted: bool = True):
+    tabs = host_tables(cfg)
+    flat = flat_from_tables(tabs)
+    state_np = np.zeros(cfg.total_rows, dtype=np.float32)
+    if state_kind == "hash":
+        state_np = W.state_rows(cfg, torch.arange(cfg.total_rows)).numpy()
+    state = torch.from_numpy(state_np.copy()).cuda()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    reports = []
+    for step in range(steps):
+        idx, off = W.make_batch(cfg, step)
+        gout = W.make_grad_out(cfg, step)
+        ws = tbe.alloc_workspace(cfg.B, max(1, idx.numel()))
+        reports.append(check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws, check_sorted,
+                                  same_inputs=(step == 0)))
+    tbe.close()
+    return reports
