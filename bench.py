@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused table-batched embedding step on one MI355X.
+
+One "step" = tbe_forward + tbe_backward_rowwise_adagrad over one synthetic batch, all inputs resident in
+HBM before the timed region.  Prints ONE JSON line: whole-job lookups/s, the roofline record of the
+dominant kernel (duration measured live with HIP events on the launch stream) and the CPU oracle timed on
+a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C1|C3|C4|C5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
+# known size); see the profile summaries under profiles/.  None = not measured for that workload/kernel.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def realised_unique(cfg, batches, torch):
+    """Per batch: (U_t per table) - statistics of the inputs, needed for the algorithmic byte counts."""
+    out = []
+    for idx, off in batches:
+        bounds = off[:: cfg.B].tolist()
+        out.append([int(torch.unique(idx[bounds[t]:bounds[t + 1]]).numel()) for t in range(cfg.T)])
+    return out
+
+
+def algorithmic_bytes(cfg, nnz, U_t):
+    """Compulsory bytes of each kernel for one batch: every distinct row once, every index once, the pooled
+    output / upstream gradient once, row and moment read-modify-write once per unique row."""
+    wb = 4 if cfg.weight_dtype == "f32" else 2
+    nb = cfg.T * cfg.B + 1
+    rows_bytes = sum(u * d * wb for u, d in zip(U_t, cfg.D))
+    U = sum(U_t)
+    dense = cfg.B * cfg.sum_D * 4
+    return {
+        "forward_pool": rows_bytes + nnz * 8 + nb * 8 + dense,
+        "linearize": nnz * 8 + nb * 8 + nnz * 12,                  # ids + offsets in; key, position, bag out
+        "radix_hist": nnz * 4,
+        "radix_scatter": nnz * 16,                                  # (key, position) in and out
+        "radix_binscan": 0,
+        "rle_count": nnz * 4,
+        "rle_scan": 0,
+        "rle_write": nnz * 4 + U * 8,
+        "seg_schedule": U * 4,
+        # gradient once, sorted positions and their bags, row + moment read-modify-write per unique row
+        "seg_update": dense + nnz * 8 + U * 8 + 2 * rows_bytes + 8 * U,
+        "seg_long_partial": 0,
+        "seg_long_update": 0,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--pool", type=int, default=4, help="pre-generated batches rotated through")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures ONE GPU: this path has no collectives (the cross-replica weight/moment averaging and "
+              "the all-to-all of the paper sit outside it). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    from paper_2508_03854_amd import TBE
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = W.config(args.workload)
+    log("workload:", W.describe(cfg))
+
+    # ---- inputs, generated directly in HBM
+    t0 = time.time()
+    flat = torch.empty(cfg.total_elems, dtype=cfg.torch_weight_dtype, device=dev)
+    W.fill_weights(cfg, flat)
+    state = torch.zeros(cfg.total_rows, dtype=torch.float32, device=dev)
+    pool = max(1, args.pool)
+    batches = W.make_batches(cfg, list(range(pool)), device=dev)
+    n_go = pool if cfg.B * cfg.sum_D * 4 * pool < 16e9 else 2
+    gouts = [W.make_grad_out(cfg, k, device=dev) for k in range(n_go)]
+    out = torch.empty(cfg.B, cfg.sum_D, dtype=torch.float32, device=dev)
+    max_nnz = max(int(i.numel()) for i, _ in batches)
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, max_nnz)
+    torch.cuda.synchronize()
+    log(f"inputs ready in {time.time() - t0:.1f}s; nnz/batch ~ {max_nnz}; workspace {ws.numel() / 1e6:.1f} MB")
+
+    def step(k):
+        idx, off = batches[k % pool]
+        tbe.forward(flat, idx, off, cfg.B, cfg.pooling, out=out)
+        tbe.backward_rowwise_adagrad(gouts[k % n_go], idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr,
+                                     eps=cfg.eps, momentum_scale=cfg.c)
+
+    # ---- warm-up (also makes the moments non-zero), then the timed region
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    assert not tbe.poll_index_error()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    lookups = sum(int(batches[(args.warmup + k) % pool][0].numel()) for k in range(args.steps))
+    value = lookups / elapsed
+    ms_per_step = 1e3 * elapsed / max(1, args.steps)
+
+    # ---- per-kernel durations with HIP events on the launch stream (separate loop: events add launch gaps)
+    prof_steps = max(2, min(args.steps, 2 * pool))
+    per_kernel = {}
+    for k in range(prof_steps):
+        tbe.timing_enable(True)
+        step(args.warmup + args.steps + k)
+        for name, ms in tbe.timing_read():
+            d = per_kernel.setdefault(name, {"launches": 0, "ms": 0.0})
+            d["launches"] += 1
+            d["ms"] += ms
+    tbe.timing_enable(False)
+    U_all = realised_unique(cfg, batches, torch)
+    nnz_all = [int(i.numel()) for i, _ in batches]
+    used = [(args.warmup + args.steps + k) % pool for k in range(prof_steps)]
+    alg = {}
+    for k in used:
+        for name, b in algorithmic_bytes(cfg, nnz_all[k], U_all[k]).items():
+            alg[name] = alg.get(name, 0.0) + b / len(used)   # mean over the profiled batches, per step
+    kernels = {}
+    for name, d in per_kernel.items():
+        per_step_launches = d["launches"] / prof_steps
+        avg_ms = d["ms"] / d["launches"]
+        bytes_per_launch = alg.get(name, 0.0)
+        kernels[name] = {"launches_per_step": per_step_launches, "avg_ms": avg_ms, "ms_per_step": d["ms"] / prof_steps,
+                         "alg_bytes_per_launch": bytes_per_launch,
+                         "alg_GBps": bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0}
+    dominant = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    dk = kernels[dominant]
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": dk["alg_GBps"] / HBM_PEAK_GBPS, "avg_launch_ms": dk["avg_ms"],
+                "alg_bytes_per_launch": dk["alg_bytes_per_launch"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))}
+    fwd_ms = kernels.get("forward_pool", {}).get("ms_per_step", 0.0)
+    kernel_ms = sum(k["ms_per_step"] for k in kernels.values())
+    step_alg_bytes = sum(alg.get(n, 0.0) * kernels[n]["launches_per_step"] for n in kernels)
+    # compulsory bytes of one whole step: the forward set + the backward set (ids are read once more by linearize)
+    compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * 8
+
+    # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1): whole tables, full batch size,
+    #      as many leading tables as fit the time budget
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        oracle.build()
+        idx, off = batches[0]
+        bounds = off[:: cfg.B].tolist()
+        woff = cfg.w_offsets()
+        # first table alone to estimate the cost per lookup, then extend to the budget
+        def sample(nt):
+            tabs = []
+            for t in range(nt):
+                a = flat[woff[t]:woff[t + 1]].view(cfg.rows[t], cfg.D[t]).cpu().numpy()
+                tabs.append(np.ascontiguousarray(a))
+            i_np = idx[:bounds[nt]].cpu().numpy()
+            o_np = off[: nt * cfg.B + 1].cpu().numpy()
+            doff = cfg.D_offsets()[nt]
+            g_np = np.ascontiguousarray(gouts[0][:, :doff].cpu().numpy())
+            st = np.ascontiguousarray(state[: cfg.row_base()[nt]].cpu().numpy())
+            return tabs, st, g_np, i_np, o_np
+
+        def run(nt, reps):
+            tabs, st, g_np, i_np, o_np = sample(nt)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                oracle.forward(tabs, i_np, o_np, cfg.B, cfg.pooling)
+                oracle.backward_rowwise_adagrad(tabs, st, g_np, i_np, o_np, cfg.B, cfg.pooling, cfg.lr, cfg.eps, cfg.c,
+                                                want_indices=False)
+            return time.perf_counter() - t0, int(i_np.size) * reps
+
+        t1, n1 = run(1, 1)
+        per_lookup = t1 / max(1, n1)
+        total_nnz = int(idx.numel())
+        budget_lookups = args.cpu_seconds / max(per_lookup, 1e-12)
+        if budget_lookups >= total_nnz:
+            nt, reps = cfg.T, max(1, int(budget_lookups // total_nnz))
+        else:
+            nt = 1
+            while nt < cfg.T and bounds[nt + 1] <= budget_lookups:
+                nt += 1
+            reps = 1
+        secs, n = run(nt, min(reps, 50))
+        cpu = {"value": n / secs, "unit": "lookups/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {nt} of {cfg.T} tables at full batch size B={cfg.B}, {min(reps, 50)} pass(es), "
+                         f"{n} lookups in {secs:.1f}s, fwd+bwd, single thread",
+               "seconds": secs}
+
+    result = {
+        "metric": "lookups/sec, fused TBE fwd+bwd+rowwise AdaGrad (achieved HBM GB/s in roofline)",
+        "value": value, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {W.describe(cfg)}", "weight_dtype": cfg.weight_dtype,
+                   "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
+                       sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
+                   "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "step_breakdown": {"forward_ms": fwd_ms, "backward_ms": kernel_ms - fwd_ms, "sum_kernel_ms": kernel_ms,
+                           "compulsory_bytes_per_step": compulsory,
+                           "compulsory_GBps_at_measured_step": compulsory / (ms_per_step * 1e-3) / 1e9,
+                           "all_kernels_alg_bytes_per_step": step_alg_bytes},
+        "kernels": kernels,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
