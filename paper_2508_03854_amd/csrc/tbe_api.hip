@@ -20,12 +20,11 @@ Workspace carve(const tbe_handle* h, int64_t N) {
         off = align256(off + bytes);
         return at;
     };
-    w.keys[0] = take(4 * n);
-    w.keys[1] = take(4 * n);
-    w.vals[0] = take(4 * n);
-    w.vals[1] = take(4 * n);
+    w.keys[0] = take(4 * (n + 1));
+    w.keys[1] = take(4 * (n + 1));
+    w.vals[0] = take(4 * (n + 1));
+    w.vals[1] = take(4 * (n + 1));
     w.bag_of_pos = take(4 * n);
-    w.unique_rows = take(4 * n);
     w.seg_start = take(4 * (n + 1));
     // radix: G blocks, each owning a contiguous slice that is a whole number of tiles
     int64_t tiles = ((int64_t)n + kRadixTile - 1) / kRadixTile;
@@ -220,12 +219,9 @@ tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_o
     int buf = 0;
     e = launch_radix_sort(h, w, ws, nnz, &buf, s);
     if (e != hipSuccess) return TBE_EHIP;
-    const uint32_t* ks = reinterpret_cast<const uint32_t*>(ws + w.keys[buf]);
-    const uint32_t* vs = reinterpret_cast<const uint32_t*>(ws + w.vals[buf]);
-    e = launch_run_lengths(h, w, ws, ks, nnz, s);
+    e = launch_run_lengths(h, w, ws, buf, nnz, s);
     if (e != hipSuccess) return TBE_EHIP;
-    e = launch_segment_update(h, w, ws, ks, vs, grad_out, offsets, B, nnz, pooling, lr, eps, momentum_scale, tables,
-                              state, s);
+    e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, offsets, B, pooling, lr, eps, momentum_scale, tables, state, s);
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
@@ -241,7 +237,7 @@ tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int
     char* ws = static_cast<char*>(workspace);
     if (keys_sorted) *keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[buf]);
     if (vals_sorted) *vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[buf]);
-    if (unique_rows) *unique_rows = reinterpret_cast<const uint32_t*>(ws + w.unique_rows);
+    if (unique_rows) *unique_rows = reinterpret_cast<const uint32_t*>(ws + w.vals[buf ^ 1]);
     if (seg_start) *seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
     if (num_unique) *num_unique = reinterpret_cast<const uint32_t*>(ws + w.counters);
     return TBE_OK;

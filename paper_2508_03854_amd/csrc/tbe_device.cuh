@@ -61,6 +61,12 @@ struct RowIO;
 template <>
 struct RowIO<float> {
     static constexpr int kVec = 4;
+    using raw_t = float4;  // a fragment as it sits in registers between the load and its use
+    static __device__ __forceinline__ raw_t load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ __forceinline__ raw_t zero_raw() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ void accumulate(const raw_t& r, float (&acc)[4]) {
+        acc[0] += r.x; acc[1] += r.y; acc[2] += r.z; acc[3] += r.w;
+    }
     static __device__ __forceinline__ void load(const float* p, float (&x)[4]) {
         const float4 v = *reinterpret_cast<const float4*>(p);
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
@@ -75,6 +81,17 @@ struct RowIO<float> {
 template <>
 struct RowIO<__half> {
     static constexpr int kVec = 8;
+    using raw_t = uint4;
+    static __device__ __forceinline__ raw_t load_raw(const __half* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ __forceinline__ raw_t zero_raw() { return make_uint4(0u, 0u, 0u, 0u); }
+    static __device__ __forceinline__ void accumulate(const raw_t& r, float (&acc)[8]) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += __half2float(__ushort_as_half((unsigned short)(w[i] & 0xFFFFu)));
+            acc[2 * i + 1] += __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+        }
+    }
     static __device__ __forceinline__ void load(const __half* p, float (&x)[8]) {
         const uint4 raw = *reinterpret_cast<const uint4*>(p);
         const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};

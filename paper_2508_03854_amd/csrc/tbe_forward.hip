@@ -12,13 +12,20 @@
 namespace tbe {
 
 constexpr int kFwdThreads = 256;
-constexpr int kFwdUnroll = 4;
+#ifndef TBE_FWD_U
+#define TBE_FWD_U 4
+#endif
+#ifndef TBE_FWD_WAVES
+#define TBE_FWD_WAVES 8
+#endif
 
-template <typename WT, int NC, bool MEAN>
+// NC = number of 64-lane column chunks a row needs (1 when D <= 64 * kVec); U = rows in flight per group.
+template <typename WT, int NC, int U, bool MEAN>
 __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const int D, const int64_t R,
                                             const int64_t* __restrict__ indices, const int64_t start,
                                             const int64_t end, float* __restrict__ out_row, int32_t* err) {
     constexpr int V = RowIO<WT>::kVec;
+    using raw_t = typename RowIO<WT>::raw_t;
     const int lane = lane_id();
     const int nl = (D + V - 1) / V;  // lanes needed by one row
     const int LPR = nl >= kWave ? kWave : pow2ceil64(nl);
@@ -40,34 +47,24 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
             if (id >= 0 && id < R) my = (int32_t)id;
             else atomicOr(err, 1);
         }
-        for (int k0 = 0; k0 < n; k0 += kFwdUnroll * G) {
-            int32_t id[kFwdUnroll];
+        for (int k0 = 0; k0 < n; k0 += U * G) {
+            raw_t x[U][NC];
 #pragma unroll
-            for (int u = 0; u < kFwdUnroll; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int k = k0 + u * G + sub;
                 const int32_t got = __shfl(my, k & (kWave - 1), kWave);
-                id[u] = (k < n) ? got : -1;
-            }
-            float x[kFwdUnroll][NC][V];
-#pragma unroll
-            for (int u = 0; u < kFwdUnroll; ++u) {
+                const int32_t id = (k < n) ? got : -1;
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const int col = lc + c * kWave * V;
-                    if (id[u] >= 0 && col < D) {
-                        RowIO<WT>::load(table + (int64_t)id[u] * D + col, x[u][c]);
-                    } else {
-#pragma unroll
-                        for (int v = 0; v < V; ++v) x[u][c][v] = 0.f;
-                    }
+                    x[u][c] = (id >= 0 && col < D) ? RowIO<WT>::load_raw(table + (int64_t)id * D + col)
+                                                   : RowIO<WT>::zero_raw();
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kFwdUnroll; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int c = 0; c < NC; ++c)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) acc[c][v] += x[u][c][v];
+                for (int c = 0; c < NC; ++c) RowIO<WT>::accumulate(x[u][c], acc[c]);
         }
     }
     // fold the groups
@@ -98,17 +95,14 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
     }
 }
 
-template <typename WT, bool MEAN>
-__global__ __launch_bounds__(kFwdThreads) void forward_kernel(const WT* __restrict__ weights,
-                                                              const int64_t* __restrict__ indices,
-                                                              const int64_t* __restrict__ offsets,
-                                                              const int32_t* __restrict__ D_off,
-                                                              const int64_t* __restrict__ w_off,
-                                                              const int64_t* __restrict__ row_base, const int32_t B,
-                                                              const int64_t nbags, const int64_t nnz,
-                                                              const int32_t sumD,
-                                                              float* __restrict__ out, int32_t* err) {
-    constexpr int V = RowIO<WT>::kVec;
+// One kernel per NC so that the common narrow-row case (NC = 1) keeps its register count low enough for
+// 8 wavefronts per SIMD; the host picks the kernel from the widest table of the handle.
+template <typename WT, int NC, int U, bool MEAN>
+__global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forward_kernel(
+    const WT* __restrict__ weights, const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
+    const int32_t B, const int64_t nbags, const int64_t nnz, const int32_t sumD, float* __restrict__ out,
+    int32_t* err) {
     const int64_t bag = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
     if (bag >= nbags) return;
     const int32_t t = (int32_t)(bag / B);
@@ -121,14 +115,20 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(const WT* __restri
     int64_t end = offsets[bag + 1];
     start = start < 0 ? 0 : (start > nnz ? nnz : start);
     end = end < start ? start : (end > nnz ? nnz : end);
-    const WT* table = weights + w_off[t];
-    float* out_row = out + (int64_t)b * sumD + d0;
-    if (D <= kWave * V)
-        forward_bag<WT, 1, MEAN>(table, D, R, indices, start, end, out_row, err);
-    else if (D <= 2 * kWave * V)
-        forward_bag<WT, 2, MEAN>(table, D, R, indices, start, end, out_row, err);
+    forward_bag<WT, NC, U, MEAN>(weights + w_off[t], D, R, indices, start, end, out + (int64_t)b * sumD + d0, err);
+}
+
+template <typename WT, int NC, int U>
+static void launch_forward_nc(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
+                              const int64_t* offsets, int32_t B, int64_t nbags, int64_t nnz, bool mean, float* out,
+                              dim3 grid, hipStream_t s) {
+    const WT* w = static_cast<const WT*>(tables);
+    if (mean)
+        forward_kernel<WT, NC, U, true><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
+                                                                     h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
     else
-        forward_bag<WT, 4, MEAN>(table, D, R, indices, start, end, out_row, err);
+        forward_kernel<WT, NC, U, false><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
+                                                                      h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
 }
 
 hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
@@ -136,25 +136,16 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     const int64_t nbags = (int64_t)h->T * B;
     if (nbags == 0) return hipSuccess;
     const int wpb = kFwdThreads / kWave;
-    const dim3 grid((unsigned)((nbags + wpb - 1) / wpb)), block(kFwdThreads);
+    const dim3 grid((unsigned)((nbags + wpb - 1) / wpb));
     LaunchTimer tm(h, s, "forward_pool");
     const bool mean = pooling == TBE_MEAN;
     if (h->dtype == TBE_F32) {
-        const float* w = static_cast<const float*>(tables);
-        if (mean)
-            forward_kernel<float, true><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, B,
-                                                               nbags, nnz, h->sumD, out, h->d_err);
-        else
-            forward_kernel<float, false><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
-                                                                B, nbags, nnz, h->sumD, out, h->d_err);
+        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
+        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
+        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
     } else {
-        const __half* w = static_cast<const __half*>(tables);
-        if (mean)
-            forward_kernel<__half, true><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
-                                                                B, nbags, nnz, h->sumD, out, h->d_err);
-        else
-            forward_kernel<__half, false><<<grid, block, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
-                                                                 h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
+        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
+        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
     }
     tm.done();
     return hipGetLastError();

@@ -51,8 +51,10 @@ namespace tbe {
 
 // Workspace carving for a batch of N lookups (all offsets in bytes, 256-byte aligned).
 struct Workspace {
-    size_t keys[2], vals[2], bag_of_pos, unique_rows, seg_start, radix_hist, bin_tot, rle_counts, counters, long_list,
-        chunk_desc, partial, total;
+    // keys/vals: radix double buffers of N+1 words each.  After the sort the buffer pair that does not hold the
+    // result is reused: keys[spare] <- bag id of every sorted position, vals[spare] <- unique_rows.
+    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_list, chunk_desc,
+        partial, total;
     int radix_blocks;     // G
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;
@@ -77,11 +79,10 @@ hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const i
                             uint32_t* keys, uint32_t* vals, uint32_t* bag_of_pos, hipStream_t s);
 // sorts (keys[0], vals[0]) of the workspace; returns in *result_buf which buffer (0/1) holds the result
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted, int64_t N,
-                              hipStream_t s);
-hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted,
-                                 const uint32_t* vals_sorted, const float* grad_out, const int64_t* offsets, int32_t B,
-                                 int64_t N, tbe_pooling pooling, float lr, float eps, float c, void* tables, float* state,
-                                 hipStream_t s);
+// `sorted` is the buffer index (0/1) that holds the sorted (key, position) pairs; the other pair is overwritten
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);
+hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const float* grad_out,
+                                 const int64_t* offsets, int32_t B, tbe_pooling pooling, float lr, float eps, float c,
+                                 void* tables, float* state, hipStream_t s);
 
 }  // namespace tbe

@@ -342,16 +342,26 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
     }
 }
 
-__global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys, const int64_t N,
+// Also resolves, for every sorted position, the bag that owns it (bag_sorted[i] = bag_of_pos[vals[i]]), so that
+// the gradient kernels read bag ids with coalesced loads instead of chasing two dependent gathers per lookup.
+__global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys,
+                                                                const uint32_t* __restrict__ vals,
+                                                                const uint32_t* __restrict__ bag_of_pos, const int64_t N,
                                                                 const uint32_t* __restrict__ block_base,
                                                                 uint32_t* __restrict__ unique_rows,
-                                                                uint32_t* __restrict__ seg_start) {
+                                                                uint32_t* __restrict__ seg_start,
+                                                                uint32_t* __restrict__ bag_sorted) {
     __shared__ uint32_t s_run[kRleRuns];
     const int lane = lane_id();
     const int w = threadIdx.x >> 6;
     const uint64_t lt = lanemask_lt();
     const int64_t base = (int64_t)blockIdx.x * kRleTile;
     uint64_t heads[kRleItems];
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) {
+        const int64_t i = base + k * kRleThreads + threadIdx.x;
+        if (i < N) bag_sorted[i] = bag_of_pos[vals[i]];
+    }
 #pragma unroll
     for (int k = 0; k < kRleItems; ++k) {
         heads[k] = __ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N));
@@ -376,11 +386,14 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
     }
 }
 
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, const uint32_t* keys_sorted, int64_t N,
-                              hipStream_t s) {
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s) {
+    const uint32_t* keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[sorted]);
+    const uint32_t* vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[sorted]);
+    const uint32_t* bag_of_pos = reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos);
     uint32_t* counts = reinterpret_cast<uint32_t*>(ws + w.rle_counts);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
-    uint32_t* unique_rows = reinterpret_cast<uint32_t*>(ws + w.unique_rows);
+    uint32_t* bag_sorted = reinterpret_cast<uint32_t*>(ws + w.keys[sorted ^ 1]);
+    uint32_t* unique_rows = reinterpret_cast<uint32_t*>(ws + w.vals[sorted ^ 1]);
     uint32_t* seg_start = reinterpret_cast<uint32_t*>(ws + w.seg_start);
     {
         LaunchTimer tm(h, s, "rle_count");
@@ -394,7 +407,8 @@ hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws,
     }
     {
         LaunchTimer tm(h, s, "rle_write");
-        rle_write_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, N, counts, unique_rows, seg_start);
+        rle_write_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, vals_sorted, bag_of_pos, N, counts, unique_rows,
+                                                              seg_start, bag_sorted);
         tm.done();
     }
     return hipGetLastError();
