@@ -27,6 +27,17 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES = {}
 
 
+def profiler_region(resume: bool) -> None:
+    """Under `rocprofv3 --selected-regions` only the code between resume and pause is profiled; the input
+    generation (tens of thousands of torch kernels) stays outside.  A no-op when the library is absent."""
+    import ctypes
+    try:
+        lib = ctypes.CDLL("librocprofiler-sdk-roctx.so")
+        (lib.roctxProfilerResume if resume else lib.roctxProfilerPause)(ctypes.c_uint64(0))
+    except OSError:
+        pass
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -74,6 +85,9 @@ def main():
     ap.add_argument("--pool", type=int, default=4, help="pre-generated batches rotated through")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows-scale", type=float, default=1.0,
+                    help="shrink every table's row count (profiling aid only; the result is then NOT the named workload)")
+    ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures ONE GPU: this path has no collectives (the cross-replica weight/moment averaging and "
@@ -87,16 +101,19 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    cfg = W.config(args.workload)
-    log("workload:", W.describe(cfg))
+    cfg = W.config(args.workload, rows_scale=args.rows_scale)
+    log("workload:", W.describe(cfg), "" if args.rows_scale == 1.0 else f"[rows scaled by {args.rows_scale}]")
 
     # ---- inputs, generated directly in HBM
     t0 = time.time()
     flat = torch.empty(cfg.total_elems, dtype=cfg.torch_weight_dtype, device=dev)
+    log("allocated tables")
     W.fill_weights(cfg, flat)
+    log("tables filled")
     state = torch.zeros(cfg.total_rows, dtype=torch.float32, device=dev)
     pool = max(1, args.pool)
     batches = W.make_batches(cfg, list(range(pool)), device=dev)
+    log("batches drawn")
     n_go = pool if cfg.B * cfg.sum_D * 4 * pool < 16e9 else 2
     gouts = [W.make_grad_out(cfg, k, device=dev) for k in range(n_go)]
     out = torch.empty(cfg.B, cfg.sum_D, dtype=torch.float32, device=dev)
@@ -112,6 +129,7 @@ def main():
         tbe.backward_rowwise_adagrad(gouts[k % n_go], idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr,
                                      eps=cfg.eps, momentum_scale=cfg.c)
 
+    profiler_region(True)
     # ---- warm-up (also makes the moments non-zero), then the timed region
     for k in range(args.warmup):
         step(k)
@@ -136,7 +154,20 @@ def main():
             d = per_kernel.setdefault(name, {"launches": 0, "ms": 0.0})
             d["launches"] += 1
             d["ms"] += ms
+    # streaming-copy calibration: achievable bandwidth, and the known-traffic kernel for counter scaling
+    copy_gbps = None
+    if args.copy_mib > 0:
+        a_buf = torch.empty(args.copy_mib << 18, dtype=torch.float32, device=dev).normal_()
+        b_buf = torch.empty_like(a_buf)
+        tbe.timing_enable(True)
+        for _ in range(4):
+            tbe.calibration_copy(b_buf, a_buf)
+        ms = [m for n, m in tbe.timing_read() if n == "calibration_copy"][1:]
+        copy_gbps = 2.0 * a_buf.numel() * 4 / (sum(ms) / len(ms) * 1e-3) / 1e9
+        del a_buf, b_buf
     tbe.timing_enable(False)
+    torch.cuda.synchronize()
+    profiler_region(False)
     U_all = realised_unique(cfg, batches, torch)
     nnz_all = [int(i.numel()) for i, _ in batches]
     used = [(args.warmup + args.steps + k) % pool for k in range(prof_steps)]
@@ -218,7 +249,8 @@ def main():
         "value": value, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {W.describe(cfg)}", "weight_dtype": cfg.weight_dtype,
+        "config": {"workload": (f"{cfg.name}: " if args.rows_scale == 1.0 else f"{cfg.name} with rows x{args.rows_scale}: ")
+                   + W.describe(cfg), "weight_dtype": cfg.weight_dtype,
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
                    "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c},
@@ -228,6 +260,7 @@ def main():
                            "compulsory_bytes_per_step": compulsory,
                            "compulsory_GBps_at_measured_step": compulsory / (ms_per_step * 1e-3) / 1e9,
                            "all_kernels_alg_bytes_per_step": step_alg_bytes},
+        "measured_copy_GBps": copy_gbps,
         "kernels": kernels,
     }
     print(json.dumps(result))

@@ -115,6 +115,12 @@ tbe_status tbe_timing_enable(tbe_handle* h, int enable);
 tbe_status tbe_timing_count(tbe_handle* h, int32_t* n);
 tbe_status tbe_timing_read(tbe_handle* h, int32_t i, const char** name, float* ms);
 
+/* Measurement aid, not a step of the method: a plain streaming copy of `bytes` bytes (multiple of 16, both
+ * pointers DEVICE and 16-byte aligned) on `hip_stream`.  Profiles use it as the kernel of known traffic
+ * that hardware byte counters are scaled by, and the benchmark reports its rate as the achievable
+ * streaming bandwidth next to the published peak.  Recorded by the timing facility as "calibration_copy". */
+tbe_status tbe_calibration_copy(tbe_handle* h, void* dst, const void* src, size_t bytes, void* hip_stream);
+
 const char* tbe_status_string(tbe_status s);
 
 #ifdef __cplusplus

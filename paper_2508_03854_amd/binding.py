@@ -20,7 +20,7 @@ SUM, MEAN = 0, 1
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
            "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable", "tbe_timing_count", "tbe_timing_read",
-           "tbe_status_string"]
+           "tbe_calibration_copy", "tbe_status_string"]
 
 
 class TbeError(RuntimeError):
@@ -66,6 +66,8 @@ def load_library():
     L.tbe_timing_count.argtypes = [vp, ctypes.POINTER(i32)]
     L.tbe_timing_read.restype = ctypes.c_int
     L.tbe_timing_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(f32)]
+    L.tbe_calibration_copy.restype = ctypes.c_int
+    L.tbe_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
     L.tbe_status_string.restype = ctypes.c_char_p
     L.tbe_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -196,6 +198,21 @@ class TBE:
         return {"keys_sorted": view(ptrs[0], nnz), "vals_sorted": view(ptrs[1], nnz),
                 "unique_rows": view(ptrs[2], U), "seg_start": view(ptrs[3], U + 1), "num_unique": U}
 
+    def debug_sorted_device(self, workspace: torch.Tensor, B: int, nnz: int) -> Dict[str, torch.Tensor]:
+        """Same by-products as device tensors (int64 copies), for checks that stay on the GPU at full size."""
+        ptrs = [ctypes.c_void_p() for _ in range(5)]
+        _check(self._lib.tbe_debug_sorted(self._h, workspace.data_ptr(), int(B), int(nnz),
+                                          *[ctypes.byref(p) for p in ptrs]), "tbe_debug_sorted")
+        base = workspace.data_ptr()
+
+        def view(p: ctypes.c_void_p, n: int) -> torch.Tensor:
+            off = p.value - base
+            return workspace[off:off + 4 * n].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+
+        U = int(view(ptrs[4], 1).item())
+        return {"keys_sorted": view(ptrs[0], nnz), "vals_sorted": view(ptrs[1], nnz),
+                "unique_rows": view(ptrs[2], U), "seg_start": view(ptrs[3], U + 1), "num_unique": U}
+
     # ---- tbe_poll_index_error
     def poll_index_error(self) -> bool:
         st = self._lib.tbe_poll_index_error(self._h)
@@ -203,6 +220,14 @@ class TBE:
             return True
         _check(st, "tbe_poll_index_error")
         return False
+
+    # ---- tbe_calibration_copy
+    def calibration_copy(self, dst: torch.Tensor, src: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+        nbytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != nbytes or not (dst.is_cuda and src.is_cuda):
+            raise ValueError("dst and src must be device tensors of the same byte size")
+        _check(self._lib.tbe_calibration_copy(self._h, dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)),
+               "tbe_calibration_copy")
 
     # ---- tbe_timing_*
     def timing_enable(self, on: bool = True) -> None:

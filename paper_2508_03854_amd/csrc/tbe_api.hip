@@ -36,7 +36,8 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.bin_tot = take(4 * 256);
     w.rle_blocks = (int)(((int64_t)n + kRleTile - 1) / kRleTile);
     w.rle_counts = take(4 * (size_t)(w.rle_blocks + 1));
-    w.counters = take(4 * 16);
+    w.counters = take(4 * kCounterWords);
+    // a long row (> kSegChunk lookups) needs ceil(len / kSegChunk) <= 2 * len / kSegChunk chunks
     w.cap_long = (int64_t)n / (kSegChunk + 1) + 1;
     w.cap_chunks = 2 * ((int64_t)n / kSegChunk) + 2;
     w.long_list = take(4 * 3 * (size_t)w.cap_long);
@@ -61,6 +62,12 @@ LaunchTimer::LaunchTimer(const tbe_handle* h_, hipStream_t s_, const char* name)
 
 void LaunchTimer::done() {
     if (slot >= 0) (void)hipEventRecord(h->slots[slot].end, s);
+}
+
+__global__ __launch_bounds__(256) void calibration_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                               const size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
 static int bits_for(uint64_t v) {  // number of bits needed to represent v (>= 1)
@@ -253,6 +260,16 @@ tbe_status tbe_poll_index_error(tbe_handle* h) {
         return TBE_EINDEX;
     }
     return TBE_OK;
+}
+
+tbe_status tbe_calibration_copy(tbe_handle* h, void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!h || !dst || !src || (bytes & 15) != 0 || !aligned(dst, 16) || !aligned(src, 16)) return TBE_EINVAL;
+    if (bytes == 0) return TBE_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LaunchTimer tm(h, s, "calibration_copy");
+    calibration_copy_kernel<<<256 * 16, 256, 0, s>>>(static_cast<float4*>(dst), static_cast<const float4*>(src), bytes / 16);
+    tm.done();
+    return hipGetLastError() == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
 tbe_status tbe_timing_enable(tbe_handle* h, int enable) {

@@ -16,6 +16,7 @@ constexpr int kRadixTile = 2048;       // elements per radix-sort tile (256 thre
 constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous slice of the input
 constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile
+constexpr int kCounterWords = 64;      // device counters: [0]=U [1]=long rows [2]=chunk slots
 
 struct TimingSlot {
     const char* name;

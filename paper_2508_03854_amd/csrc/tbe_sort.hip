@@ -336,9 +336,9 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
     }
     if (threadIdx.x == 0) {
         counters[0] = carry;  // num_unique
-        counters[1] = 0u;     // number of long rows
-        counters[2] = 0u;     // number of long-row chunks
         seg_start[carry] = (uint32_t)N;
+    } else if (threadIdx.x < kCounterWords) {
+        counters[threadIdx.x] = 0u;  // long-row count, chunk slots
     }
 }
 

@@ -1,0 +1,150 @@
+"""Parity at the full benchmark sizes (one GPU's shard of 100-200 GB), in the launch configuration bench.py
+times.  The oracle cannot hold these tables, so it is applied to sampled outputs one by one (a bag of the
+forward; a row of the backward, whose gradient it derives from its definition by scanning the table's
+positions), and the integer by-products are checked through properties that pin them uniquely at any size."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _close(got, ref, rtol, scale, what):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    err = np.abs(got - ref)
+    tol = rtol * np.abs(ref) + rtol * scale
+    assert (err <= tol).all(), f"{what}: max err {err.max():.3e} (tol {tol[np.argmax(err - tol)]:.3e})"
+
+
+@pytest.mark.parametrize("name", ["C4", "C5", "C3"])
+def test_full_size_sampled_parity(name):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()          # hand back what an earlier case cached: each case needs most of the HBM
+    free, total = torch.cuda.mem_get_info()
+    cfg = W.config(name, c=2.0)
+    if cfg.weight_bytes + 30e9 > free:
+        pytest.skip(f"{name} needs {cfg.weight_bytes / 1e9:.0f} GB of HBM")
+    import oracle
+    from paper_2508_03854_amd import TBE
+    dev = "cuda"
+    print(W.describe(cfg), flush=True)
+    rng = np.random.default_rng(0)
+    f16 = cfg.weight_dtype == "f16"
+    np_w = np.float16 if f16 else np.float32
+    rtol_w = 1e-2 if f16 else 1e-5
+    B, T = cfg.B, cfg.T
+    doff, rbase, woff = cfg.D_offsets(), cfg.row_base(), cfg.w_offsets()
+
+    flat = torch.empty(cfg.total_elems, dtype=cfg.torch_weight_dtype, device=dev)
+    W.fill_weights(cfg, flat)
+    state = torch.empty(cfg.total_rows, dtype=torch.float32, device=dev)
+    W.fill_state(cfg, state, "hash")
+    state0 = state.clone()
+    idx, off = W.make_batch(cfg, 0, device=dev)
+    gout = W.make_grad_out(cfg, 0, device=dev)
+    nnz = idx.numel()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(B, nnz)
+    print("inputs ready, nnz", nnz, flush=True)
+
+    def init_rows(t, ids):
+        w = W.weight_rows(cfg, t, torch.as_tensor(ids, dtype=torch.int64))
+        return (w.to(torch.float16) if f16 else w).numpy()
+
+    # ------------------------------------------------------------------ forward, sampled bags
+    out = tbe.forward(flat, idx, off, B, cfg.pooling)
+    torch.cuda.synchronize()
+    assert not tbe.poll_index_error()
+    off_cpu = off.cpu().numpy()
+    lens = np.diff(off_cpu)
+    bags = set(rng.integers(0, T * B, size=150).tolist())
+    bags |= {0, T * B - 1, int(np.argmax(lens)), int(np.argmin(lens))}
+    for bag in sorted(bags):
+        t, b = divmod(bag, B)
+        ids = idx[off_cpu[bag]:off_cpu[bag + 1]].cpu().numpy()
+        uniq, inv = np.unique(ids, return_inverse=True)          # compact copy of just the rows this bag touches
+        ref = oracle.forward_bag(np.ascontiguousarray(init_rows(t, uniq)), inv.astype(np.int64), 0, len(ids), cfg.pooling)
+        _close(out[b, doff[t]:doff[t + 1]].cpu().numpy(), ref, 1e-5, cfg.w_scale, f"forward bag {bag}")
+    print("forward: %d sampled bags ok" % len(bags), flush=True)
+    del out
+
+    # ------------------------------------------------------------------ backward
+    tbe.backward_rowwise_adagrad(gout, idx, off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
+                                 momentum_scale=cfg.c)
+    torch.cuda.synchronize()
+    assert not tbe.poll_index_error()
+
+    # integer by-products, pinned by properties (checked on the device with library ops)
+    dbg = tbe.debug_sorted_device(ws, B, nnz)
+    ks, vs, uq, ss, U = dbg["keys_sorted"], dbg["vals_sorted"], dbg["unique_rows"], dbg["seg_start"], dbg["num_unique"]
+    bag_of = torch.repeat_interleave(torch.arange(T * B, device=dev), off[1:] - off[:-1])
+    keys = torch.tensor(rbase[:-1], device=dev)[bag_of // B] + idx        # the definition of the linearised key
+    del bag_of
+    assert bool((ks[1:] >= ks[:-1]).all()), "keys not sorted"
+    assert bool((keys[vs] == ks).all()), "payload does not carry its key"
+    same = ks[1:] == ks[:-1]
+    assert bool((vs[1:][same] > vs[:-1][same]).all()), "equal keys not in ascending position order (not stable)"
+    assert int(torch.bincount(vs, minlength=nnz).max()) == 1 and int(vs.max()) == nnz - 1, "payload is not a permutation"
+    head = torch.ones(nnz, dtype=torch.bool, device=dev)
+    head[1:] = ~same
+    assert U == int(head.sum())
+    assert bool((uq == ks[head]).all()) and bool((ss[:-1] == head.nonzero().squeeze(1)).all()) and int(ss[-1]) == nnz
+    seg_len = ss[1:] - ss[:-1]
+    print("sort / dedup / segments ok: U=%d, longest segment %d" % (U, int(seg_len.max())), flush=True)
+    del keys, same, head
+
+    # which rows were updated: moments changed exactly on unique_rows (a touched row has a nonzero gradient a.s.)
+    changed = (state != state0).nonzero().squeeze(1)
+    assert changed.numel() == U and bool((changed == uq).all()), "set of updated moments differs from unique_rows"
+    del changed
+
+    # sampled tables: the changed weight rows are exactly the ids of the batch; all other rows keep their bits
+    tables = sorted({0, T - 1, int(np.argmax(cfg.rows)), int(np.argmin(cfg.rows))} | set(rng.integers(0, T, size=2).tolist()))
+    for t in tables:
+        R, D = cfg.rows[t], cfg.D[t]
+        cur = flat[woff[t]:woff[t + 1]].view(R, D)
+        moved = torch.zeros(R, dtype=torch.bool, device=dev)
+        step = max(1, (1 << 24) // D)
+        for r0 in range(0, R, step):
+            r1 = min(R, r0 + step)
+            init = W.weight_rows(cfg, t, torch.arange(r0, r1, device=dev)).to(cfg.torch_weight_dtype)
+            moved[r0:r1] = (cur[r0:r1] != init).any(1)
+        ids_t = idx[off_cpu[t * B]:off_cpu[(t + 1) * B]]
+        touched = torch.zeros(R, dtype=torch.bool, device=dev)
+        touched[ids_t] = True
+        assert not bool((moved & ~touched).any()), f"table {t}: a row outside the batch changed"
+        # (a touched row may keep its bits only if every element's update rounds away; count such rows, expect ~none)
+        assert int((touched & ~moved).sum()) <= max(2, touched.sum().item() // 1000), f"table {t}: touched rows unchanged"
+
+        # sampled rows: hottest, around the kernel's segment-length classes, singletons
+        u_ids, cnt = torch.unique(ids_t, return_counts=True)
+        picks = {int(u_ids[torch.argmax(cnt)])}
+        for target in (1, 2, 3, 17, 64, 65, 200, 512, 513, 3000):
+            j = int(torch.argmin((cnt - target).abs()))
+            picks.add(int(u_ids[j]))
+        ids_np = ids_t.cpu().numpy()
+        off_t = off_cpu[t * B:(t + 1) * B + 1] - off_cpu[t * B]
+        g_block = np.ascontiguousarray(gout[:, doff[t]:doff[t + 1]].cpu().numpy())
+        for r in sorted(picks):
+            g, hits = oracle.row_gradient_by_scan(0, r, D, 0, g_block, ids_np, off_t, B, cfg.pooling)
+            assert hits == int(cnt[(u_ids == r).nonzero()[0, 0]])
+            row = np.ascontiguousarray(init_rows(t, [r]))
+            v = W.state_rows(cfg, torch.tensor([rbase[t] + r])).numpy().copy()
+            oracle.adagrad_row(row, 0, v, g, cfg.lr, cfg.eps, cfg.c)
+            got_w = cur[r].cpu().numpy()
+            _close(got_w, row[0], rtol_w, cfg.w_scale, f"table {t} row {r} ({hits} lookups) weights")
+            if f16:
+                a, bb = got_w.view(np.uint16).astype(np.int32), row[0].view(np.uint16).astype(np.int32)
+                oa, ob = np.where(a & 0x8000, -(a & 0x7FFF), a), np.where(bb & 0x8000, -(bb & 0x7FFF), bb)
+                assert np.abs(oa - ob).max() <= 1, f"table {t} row {r}: more than one binary16 ulp from the oracle"
+            _close(state[rbase[t] + r].item(), v[0], 1e-5, 1e-6, f"table {t} row {r} moment")
+        print("table %d (R=%d, D=%d): update set exact, %d sampled rows ok" % (t, R, D, len(picks)), flush=True)
+    tbe.close()
+    del flat, state, state0, idx, off, gout, ws, dbg, ks, vs, uq, ss, cur, moved, touched
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -231,6 +231,7 @@ def fill_weights(cfg: Config, flat: torch.Tensor, chunk_elems: int = 1 << 25) ->
             r1 = min(R, r0 + step)
             ids = torch.arange(r0, r1, dtype=torch.int64, device=flat.device)
             view[r0:r1].copy_(weight_rows(cfg, t, ids))
+        _drain(flat.device)
 
 
 def state_rows(cfg: Config, keys: torch.Tensor, scale: float = 4.0) -> torch.Tensor:
@@ -254,6 +255,13 @@ def fill_state(cfg: Config, state: torch.Tensor, kind: str = "zeros", chunk: int
 # --------------------------------------------------------------------------------------
 # bag lengths, ids, upstream gradient
 # --------------------------------------------------------------------------------------
+def _drain(device) -> None:
+    """Keep the launch queue short: generation issues tens of thousands of small kernels, and a profiler that
+    intercepts every dispatch has been seen to fall over when thousands of them are outstanding at once."""
+    if torch.device(device).type == "cuda":
+        torch.cuda.synchronize()
+
+
 def _gen(device, seed: int) -> torch.Generator:
     g = torch.Generator(device=device)
     g.manual_seed(seed)
@@ -327,6 +335,7 @@ def make_batches(cfg: Config, steps: Sequence[int], device="cpu") -> List[Tuple[
             per_step_len[k].append(L)
             per_step_ids[k].append(sampler.draw(n, g))
         del sampler
+        _drain(device)
     out = []
     for k in range(len(steps)):
         L = torch.cat(per_step_len[k])
