@@ -1,0 +1,281 @@
+"""Edge cases of the HIP path against the oracle: empty and ragged inputs, degenerate shapes, the extremes
+of the segment-length classes, unusual widths, the error path, determinism and graph replay."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+def make_cfg(rows, D, dtype="f32", B=8, pooling="sum", c=1.0, lr=0.05, eps=1e-8):
+    cfg = W.Config("edge", list(rows), list(D), dtype, B, pooling, ("fixed", 1), ("uniform",))
+    cfg.c, cfg.lr, cfg.eps = c, lr, eps
+    return cfg
+
+
+def run_custom(H, cfg, lens, ids, seed=0, state_kind="hash", steps=1):
+    """lens: T*B bag lengths; ids: concatenated table-local ids."""
+    from paper_2508_03854_amd import TBE
+    off = torch.zeros(len(lens) + 1, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.as_tensor(lens, dtype=torch.int64), 0)
+    idx = torch.as_tensor(ids, dtype=torch.int64)
+    assert off[-1] == idx.numel()
+    g = torch.Generator().manual_seed(seed)
+    tabs = H.host_tables(cfg)
+    flat = H.flat_from_tables(tabs)
+    state_np = (W.state_rows(cfg, torch.arange(cfg.total_rows)).numpy() if state_kind == "hash"
+                else np.zeros(cfg.total_rows, dtype=np.float32))
+    state = torch.from_numpy(state_np.copy()).cuda()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, max(1, idx.numel()))
+    reps = []
+    for s in range(steps):
+        gout = torch.randn(cfg.B, cfg.sum_D, generator=g, dtype=torch.float32)
+        reps.append(H.check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws, same_inputs=(s == 0)))
+    tbe.close()
+    return reps
+
+
+def test_empty_bags_everywhere_and_long_runs_of_empty_bags(H):
+    rng = np.random.default_rng(0)
+    cfg = make_cfg([50, 7, 300], [64, 32, 128], B=3000, pooling="mean")
+    lens = rng.integers(0, 3, size=3 * 3000)
+    lens[100:2900] = 0                      # 2800 empty bags in a row inside table 0
+    lens[3000:6000] = 0                     # table 1 has no lookups at all
+    lens[0] = 0
+    lens[-1] = 0
+    ids = np.concatenate([rng.integers(0, cfg.rows[t], size=int(lens[t * 3000:(t + 1) * 3000].sum())) for t in range(3)])
+    rep = run_custom(H, cfg, lens, ids)
+    assert rep[0]["U"] > 0
+
+
+def test_no_lookups_at_all(H):
+    from paper_2508_03854_amd import TBE
+    cfg = make_cfg([10, 20], [16, 8], B=5)
+    tabs = H.host_tables(cfg)
+    flat = H.flat_from_tables(tabs)
+    before = flat.clone()
+    state = torch.ones(30, device="cuda")
+    tbe = TBE(cfg.rows, cfg.D, "f32")
+    off = torch.zeros(2 * 5 + 1, dtype=torch.int64, device="cuda")
+    idx = torch.zeros(0, dtype=torch.int64, device="cuda")
+    out = tbe.forward(flat, idx, off, 5, "sum")
+    assert torch.count_nonzero(out) == 0
+    ws = tbe.alloc_workspace(5, 1)
+    tbe.backward_rowwise_adagrad(torch.randn(5, 24, device="cuda"), idx, off, 5, flat, state, ws, lr=0.1, eps=1e-8)
+    torch.cuda.synchronize()
+    assert torch.equal(flat, before) and torch.equal(state, torch.ones(30, device="cuda"))
+
+
+def test_batch_of_one_single_table_single_row(H):
+    cfg = make_cfg([1], [4], B=1)
+    run_custom(H, cfg, [5], [0, 0, 0, 0, 0])                  # one row hit five times in one bag
+    cfg = make_cfg([3], [8], B=1, dtype="f16", pooling="mean")
+    run_custom(H, cfg, [2], [2, 0])                           # max id = rows-1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("pooling", ["sum", "mean"])
+def test_segment_length_classes(H, dtype, pooling):
+    # rows hit exactly 1, 2, 63, 64, 65, 511, 512, 513, 1025 and 5000 times: every boundary of the short / medium /
+    # long classes of the segment kernels; B is large so the hits of one row spread over many bags
+    rng = np.random.default_rng(1)
+    counts = [1, 2, 63, 64, 65, 511, 512, 513, 1025, 5000, 1, 1, 3, 64, 64]
+    B = 700
+    cfg = make_cfg([len(counts) + 5, 40], [64, 256], dtype=dtype, B=B, pooling=pooling, c=4.0)
+    ids0 = np.concatenate([np.full(n, r) for r, n in enumerate(counts)])
+    rng.shuffle(ids0)
+    lens0 = rng.multinomial(len(ids0), np.ones(B) / B)
+    ids1 = rng.integers(0, 40, size=3 * B)
+    lens1 = np.full(B, 3)
+    rep = run_custom(H, cfg, np.concatenate([lens0, lens1]), np.concatenate([ids0, ids1]), steps=2)
+    assert rep[0]["max_seg"] == 5000
+
+
+def test_one_row_takes_a_hundred_thousand_lookups(H):
+    rng = np.random.default_rng(2)
+    B, n = 2048, 120_000
+    cfg = make_cfg([10], [128], B=B)
+    ids = np.where(rng.random(n) < 0.9, 3, rng.integers(0, 10, size=n))
+    lens = rng.multinomial(n, np.ones(B) / B)
+    rep = run_custom(H, cfg, lens, ids, state_kind="zeros")
+    assert rep[0]["max_seg"] > 100_000
+
+
+@pytest.mark.parametrize("dtype,Ds", [("f32", [4, 12, 20, 36, 96, 100, 160, 260, 384, 512, 1024]),
+                                      ("f16", [8, 24, 40, 96, 136, 264, 520, 1024])])
+def test_unusual_widths(H, dtype, Ds):
+    # widths that are not powers of two, narrower than a float4 group, and wider than one 64-lane pass
+    rng = np.random.default_rng(3)
+    B = 64
+    rows = [30 + 3 * i for i in range(len(Ds))]
+    cfg = make_cfg(rows, Ds, dtype=dtype, B=B, pooling="mean", c=2.0)
+    lens = rng.integers(0, 9, size=len(Ds) * B)
+    ids = np.concatenate([rng.integers(0, rows[t], size=int(lens[t * B:(t + 1) * B].sum())) for t in range(len(Ds))])
+    # make one row of the widest table long enough for the chunked path
+    run_custom(H, cfg, lens, ids)
+    cfg2 = make_cfg([5], [Ds[-1]], dtype=dtype, B=600)
+    run_custom(H, cfg2, np.full(600, 3), rng.integers(0, 2, size=1800))
+
+
+def test_invalid_ids_are_reported_and_harmless():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    import oracle
+    rows, D, B = [10, 6], [8, 16], 4
+    tbe = TBE(rows, D, "f32")
+    g = torch.Generator().manual_seed(0)
+    flat_cpu = torch.randn(10 * 8 + 6 * 16, generator=g)
+    flat = flat_cpu.cuda()
+    lens = [2, 1, 0, 3, 1, 1, 2, 1]
+    good = torch.tensor([1, 9, 4, 0, 3, 3, 5, 0, 2, 1, 5], dtype=torch.int64)
+    bad = good.clone()
+    bad[1] = 10                      # == rows[0]
+    bad[3] = -1
+    bad[8] = 6                       # == rows[1]
+    off = torch.zeros(9, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.tensor(lens), 0)
+    out = tbe.forward(flat, bad.cuda(), off.cuda(), B, "sum")
+    assert tbe.poll_index_error() and not tbe.poll_index_error()          # reported once, then cleared
+    # the forward skips invalid ids: same as the oracle on the bags with those lookups removed
+    keep = torch.ones(11, dtype=torch.bool)
+    keep[[1, 3, 8]] = False
+    lens2 = [1, 1, 0, 2, 1, 1, 1, 1]
+    off2 = np.concatenate([[0], np.cumsum(lens2)])
+    tabs = [flat_cpu[:80].view(10, 8).numpy().copy(), flat_cpu[80:].view(6, 16).numpy().copy()]
+    ref = oracle.forward(tabs, good[keep].numpy(), off2, B, "sum")
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-6, atol=1e-6)
+    # the backward gives invalid ids to no row: same as the oracle without them
+    state = torch.zeros(16, device="cuda")
+    gout = torch.randn(B, 24, generator=g)
+    ws = tbe.alloc_workspace(B, 11)
+    tbe.backward_rowwise_adagrad(gout.cuda(), bad.cuda(), off.cuda(), B, flat, state, ws, lr=0.1, eps=1e-8)
+    assert tbe.poll_index_error()
+    st = np.zeros(16, dtype=np.float32)
+    oracle.backward_rowwise_adagrad(tabs, st, gout.numpy(), good[keep].numpy(), off2, B, "sum", 0.1, 1e-8, 1.0)
+    np.testing.assert_allclose(flat.cpu().numpy(), np.concatenate([t.reshape(-1) for t in tabs]), rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(state.cpu().numpy(), st, rtol=1e-5)
+    dbg = tbe.debug_sorted(ws, B, 11)
+    valid_keys = {1, 4, 3} | {10 + 5, 10 + 0, 10 + 1}                     # table 0: ids 1,4,3,3; table 1: ids 5,0,1,5
+    assert dbg["num_unique"] == len(valid_keys) + 1
+    assert set(dbg["unique_rows"][:-1].tolist()) == valid_keys
+    assert int(dbg["unique_rows"][-1]) == 16                              # the trailing pseudo-row of invalid ids
+
+
+def test_argument_checks_return_status_codes():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE, TbeError
+    from paper_2508_03854_amd import binding as Bn
+    tbe = TBE([10], [8], "f32")
+    flat = torch.zeros(80, device="cuda")
+    state = torch.zeros(10, device="cuda")
+    idx = torch.zeros(4, dtype=torch.int64, device="cuda")
+    off = torch.tensor([0, 2, 4], dtype=torch.int64, device="cuda")
+    gout = torch.zeros(2, 8, device="cuda")
+    ws = tbe.alloc_workspace(2, 4)
+    for kw, code in ((dict(lr=float("nan"), eps=1e-8), Bn.EINVAL), (dict(lr=0.1, eps=-1.0), Bn.EINVAL),
+                     (dict(lr=0.1, eps=1e-8, momentum_scale=0.0), Bn.EINVAL),
+                     (dict(lr=0.1, eps=1e-8, momentum_scale=-2.0), Bn.EINVAL)):
+        with pytest.raises(TbeError) as e:
+            tbe.backward_rowwise_adagrad(gout, idx, off, 2, flat, state, ws, **kw)
+        assert e.value.status == code
+    with pytest.raises(TbeError) as e:
+        tbe.backward_rowwise_adagrad(gout, idx, off, 2, flat, state, ws[:256], lr=0.1, eps=1e-8)
+    assert e.value.status == Bn.EWORKSPACE
+    with pytest.raises(TbeError) as e:
+        TBE([10], [6], "f32")
+    assert e.value.status == Bn.ESHAPE
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(flat) == 0 and torch.count_nonzero(state) == 0     # nothing was launched
+
+
+def test_two_runs_agree_bit_for_bit_and_graph_replay_matches_eager():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    cfg = W.config("C3", T=6, B=512, rows_scale=2e-3, c=2.0)
+    idx, off = (x.cuda() for x in W.make_batch(cfg, 0))
+    gout = W.make_grad_out(cfg, 0).cuda()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, idx.numel())
+
+    def fresh():
+        flat = torch.empty(cfg.total_elems, device="cuda")
+        W.fill_weights(cfg, flat)
+        return flat, torch.zeros(cfg.total_rows, device="cuda")
+
+    def eager(flat, state, n):
+        outs = []
+        for _ in range(n):
+            outs.append(tbe.forward(flat, idx, off, cfg.B, cfg.pooling).clone())
+            tbe.backward_rowwise_adagrad(gout, idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr,
+                                         eps=cfg.eps, momentum_scale=cfg.c)
+        torch.cuda.synchronize()
+        return outs
+
+    f1, s1 = fresh()
+    o1 = eager(f1, s1, 3)
+    f2, s2 = fresh()
+    o2 = eager(f2, s2, 3)
+    assert torch.equal(f1, f2) and torch.equal(s1, s2) and all(torch.equal(a, b) for a, b in zip(o1, o2))
+
+    # the two hot calls record no memset and allocate nothing: capture one step, replay it three times with eager
+    # work and synchronisation in between, and compare every replay with the eager sequence
+    f3, s3 = fresh()
+    out3 = torch.empty(cfg.B, cfg.sum_D, device="cuda")
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    f_warm, s_warm = fresh()
+    with torch.cuda.stream(stream):                      # warm-up on the side stream, on scratch copies
+        tbe.forward(f_warm, idx, off, cfg.B, cfg.pooling, out=out3, stream=stream)
+        tbe.backward_rowwise_adagrad(gout, idx, off, cfg.B, f_warm, s_warm, ws, pooling=cfg.pooling, lr=cfg.lr,
+                                     eps=cfg.eps, momentum_scale=cfg.c, stream=stream)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=stream):
+        cur = torch.cuda.current_stream()
+        tbe.forward(f3, idx, off, cfg.B, cfg.pooling, out=out3, stream=cur)
+        tbe.backward_rowwise_adagrad(gout, idx, off, cfg.B, f3, s3, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
+                                     momentum_scale=cfg.c, stream=cur)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out3, o1[k]), f"replay {k}: forward differs from eager"
+        _ = (out3 * 2).sum().item()                      # unrelated eager work between replays
+    assert torch.equal(f3, f1) and torch.equal(s3, s1)
+    tbe.close()
+
+
+def test_checkpoint_resume_is_bit_identical():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    cfg = W.config("C2", T=4, B=256, rows_scale=0.02, c=4.0)
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    batches = [tuple(x.cuda() for x in W.make_batch(cfg, s)) for s in range(2)]
+    gouts = [W.make_grad_out(cfg, s).cuda() for s in range(2)]
+    ws = tbe.alloc_workspace(cfg.B, max(b[0].numel() for b in batches))
+    res = []
+    for copy_between in (False, True):
+        flat = torch.empty(cfg.total_elems, device="cuda")
+        W.fill_weights(cfg, flat)
+        state = torch.zeros(cfg.total_rows, device="cuda")
+        for s in range(2):
+            tbe.backward_rowwise_adagrad(gouts[s], batches[s][0], batches[s][1], cfg.B, flat, state, ws, lr=cfg.lr,
+                                         eps=cfg.eps, momentum_scale=cfg.c)
+            if copy_between:                                  # "checkpoint": the caller's two buffers are all the state
+                flat = flat.cpu().cuda()
+                state = state.cpu().cuda()
+        res.append((flat.clone(), state.clone()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
