@@ -68,7 +68,7 @@ def algorithmic_bytes(cfg, nnz, U_t):
         "rle_count": nnz * 4,
         "rle_scan": 0,
         "rle_write": nnz * 4 + U * 8,
-        "seg_schedule": U * 4,
+        "seg_long_list": U * 8,
         # gradient once, sorted positions and their bags, row + moment read-modify-write per unique row
         "seg_update": dense + nnz * 8 + U * 8 + 2 * rows_bytes + 8 * U,
         "seg_long_partial": 0,

@@ -10,7 +10,7 @@ namespace tbe {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Workspace carve(const tbe_handle* h, int64_t N) {
+Workspace carve(const tbe_handle* h, int64_t N, int32_t B) {
     Workspace w;
     memset(&w, 0, sizeof(w));
     const size_t n = (size_t)(N > 0 ? N : 1);
@@ -37,12 +37,23 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.rle_blocks = (int)(((int64_t)n + kRleTile - 1) / kRleTile);
     w.rle_counts = take(4 * (size_t)(w.rle_blocks + 1));
     w.counters = take(4 * kCounterWords);
-    // a long row (> kSegChunk lookups) needs ceil(len / kSegChunk) <= 2 * len / kSegChunk chunks
+    // partial sums of a long row (> kSegChunk lookups): 8 (one per XCD, 8 <= len/64), or for rows of >= 8192
+    // lookups at most len/256 + 128 <= len/256 + len/64, or ceil(len/kSegChunk) <= 2*len/kSegChunk equal shares
     w.cap_long = (int64_t)n / (kSegChunk + 1) + 1;
-    w.cap_chunks = 2 * ((int64_t)n / kSegChunk) + 2;
-    w.long_list = take(4 * 3 * (size_t)w.cap_long);
-    w.chunk_desc = take(4 * 2 * (size_t)w.cap_chunks);
+    w.cap_chunks = (int64_t)n / 64 + (int64_t)n / 256 + 2 * ((int64_t)n / kSegChunk) + 2;
+    // work units: one per long row, or len/(8*256) + 2 <= len/1024 for the heaviest, or ceil(len/512) <= len/256 shares
+    w.cap_units = w.cap_long + (int64_t)n / 1024 + (int64_t)n / 256 + 2;
+    w.unit_list = take(8 * (size_t)w.cap_units);
+    w.bounds = take(4 * (size_t)(kMaxSlices + 1) * (size_t)w.cap_long);
+    w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
+    w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);
+#ifdef TBE_GRAD_TABLE_MAJOR
+    w.grad_tm_bytes = 4 * (size_t)B * (size_t)h->sumD;
+    w.grad_tm = take(w.grad_tm_bytes);
+#else
+    (void)B;
+#endif
     w.total = off;
     return w;
 }
@@ -181,7 +192,7 @@ tbe_status tbe_workspace_bytes(const tbe_handle* h, int32_t B, int64_t max_nnz, 
     if (!h || !bytes) return TBE_EINVAL;
     const tbe_status st = check_batch(h, B, max_nnz);
     if (st != TBE_OK) return st;
-    *bytes = carve(h, max_nnz).total;
+    *bytes = carve(h, max_nnz, B).total;
     return TBE_OK;
 }
 
@@ -215,7 +226,7 @@ tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_o
         return TBE_EINVAL;
     if (nnz == 0) return TBE_OK;  // no id appears in the batch: no row has a gradient
     if (!workspace || !aligned(workspace, 256)) return TBE_EINVAL;
-    const Workspace w = carve(h, nnz);
+    const Workspace w = carve(h, nnz, B);
     if (workspace_bytes < w.total) return TBE_EWORKSPACE;
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -238,7 +249,7 @@ tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int
     if (!h || !workspace) return TBE_EINVAL;
     const tbe_status st = check_batch(h, B, nnz);
     if (st != TBE_OK) return st;
-    const Workspace w = carve(h, nnz);
+    const Workspace w = carve(h, nnz, B);
     const int passes = (h->key_bits + 7) / 8;
     const int buf = passes & 1;  // every pass flips the double buffer, starting from 0
     char* ws = static_cast<char*>(workspace);

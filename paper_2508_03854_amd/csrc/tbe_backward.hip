@@ -22,6 +22,12 @@ constexpr int kSegBlocks = 2048;  // persistent grid: waves stride over blocks o
 #define TBE_SEG_U 4
 #endif
 constexpr int kSegUnroll = TBE_SEG_U;
+#ifndef TBE_LONG_BLOCKS
+#define TBE_LONG_BLOCKS 2048
+#endif
+#ifndef TBE_SLICE_KB
+#define TBE_SLICE_KB 1024
+#endif
 
 struct RowGeom {
     int D, LPR, G, sub, lc;
@@ -57,6 +63,7 @@ struct SegArgs {
     const uint32_t* bag_sorted;   // linear bag id of every sorted position
     const int64_t* offsets;
     const float* grad_out;
+    const float* grad_tm;         // table-major copy of grad_out, or nullptr
     const int32_t* D_off;
     const int64_t* row_base;
     const int64_t* w_off;
@@ -65,11 +72,32 @@ struct SegArgs {
     float lr, eps, inv_c;
     void* tables;
     float* state;
-    uint32_t* long_list;   // [cap_long][3]  (u, slot, nchunks)
-    uint32_t* chunk_desc;  // [cap_chunks][2] (u, k)
-    float* partial;        // [cap_chunks][maxD]
+    uint32_t* long_list;   // [cap_long][4]  (u, first slot, parts | sliced flag, table)
+    float* partial;        // [cap_chunks][maxD] partial sums of long rows
+    uint2* unit_list;      // [cap_units] (position in long_list, unit index)
+    uint32_t* bounds;      // [cap_long][kMaxSlices + 1] sub-slice borders inside a sliced row's segment
+    uint32_t cap_units;
     uint32_t cap_long, cap_chunks;
 };
+
+// Where the upstream gradient of table t lives: either in the caller's [B, sum(D)] matrix (column block
+// D_off[t], row stride sum(D)), or in the table-major copy made by grad_to_table_major (block t is a
+// contiguous [B, D_t] matrix, so the slices of consecutive bags are adjacent in memory).
+struct GradView {
+    const float* base;
+    int64_t stride;
+};
+__device__ __forceinline__ GradView grad_view(const SegArgs& a, int t, int d0, int D) {
+    GradView v;
+    if (a.grad_tm) {
+        v.base = a.grad_tm + (int64_t)a.B * d0;
+        v.stride = D;
+    } else {
+        v.base = a.grad_out + d0;
+        v.stride = a.sumD;
+    }
+    return v;
+}
 
 template <bool MEAN>
 __device__ __forceinline__ float bag_scale(const int64_t* __restrict__ offsets, uint32_t bag) {
@@ -179,56 +207,281 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
     }
 }
 
-// ---- 1. find the long rows and give each of their chunks a slot in the partial buffer ------------
-__global__ __launch_bounds__(256) void seg_schedule_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+// ---- table-major copy of the upstream gradient ---------------------------------------------------------
+// grad_tm[B * D_off[t] + b * D_t + j] = grad_out[b * sum(D) + D_off[t] + j].  One workgroup row per sample,
+// float4 per thread, both sides coalesced.
+__global__ __launch_bounds__(256) void grad_to_table_major_kernel(const float* __restrict__ grad_out,
+                                                                  float* __restrict__ grad_tm,
+                                                                  const int32_t* __restrict__ D_off, const int T,
+                                                                  const int B, const int sumD) {
+    const int b = blockIdx.x;
+    const float* src = grad_out + (int64_t)b * sumD;
+    for (int col = threadIdx.x * 4; col < sumD; col += blockDim.x * 4) {
+        int lo = 0, hi = T;  // table of this column: last t with D_off[t] <= col
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (D_off[mid + 1] > col) hi = mid;
+            else lo = mid + 1;
+        }
+        const int d0 = D_off[lo];
+        const int D = D_off[lo + 1] - d0;
+        *reinterpret_cast<float4*>(grad_tm + (int64_t)B * d0 + (int64_t)b * D + (col - d0)) =
+            *reinterpret_cast<const float4*>(src + col);
+    }
+}
+
+// ---- long rows (> kSegChunk lookups): the head of the Zipf distribution ------------------------------
+// The upstream gradient block of one table (B x D_t floats, 16-32 MB at large batch sizes) is several times
+// one XCD's 4 MB L2, so the slices that hot rows gather would stream through the L2 again and again
+// (measured: random 1 KB reads run at ~28 TB/s from an L2-resident set, ~8 TB/s otherwise).  For such tables
+// every XCD owns one eighth of the bags (workgroup id mod 8 is the XCD the dispatcher picks) and walks it in
+// sub-slices of at most ~1 MB of gradient, one sub-slice per sweep over the list of hot rows; the hot rows are
+// listed table by table, so at any time an XCD works on one sub-slice of one or two tables, which stays
+// resident in its L2 while all hot rows of the table pass over it.  The stable sort left a row's lookups in
+// ascending bag order, so the lookups of a sub-slice are one contiguous range found by binary search.
+// A hot row thus has 8 partial sums, one per XCD, accumulated over the sweeps by the same workgroup.
+// Hot rows of tables whose gradient block fits the L2 anyway are cut into up to 16 equal parts instead.
+constexpr int kMaxParts = 16;
+constexpr uint32_t kSliceBytes = (uint32_t)TBE_SLICE_KB << 10;
+
+constexpr uint32_t kSlicedFlag = 0x80000000u;
+
+// number of sub-slices of a table's gradient block (power of two); >= 8 means "bag-sliced over the XCDs"
+__device__ __host__ __forceinline__ uint32_t slices_for(uint32_t B, uint32_t D) {
+    const uint64_t bytes = (uint64_t)B * D * 4u;
+    uint32_t S = 1;
+    while (S < kMaxSlices && bytes > (uint64_t)S * kSliceBytes) S <<= 1;
+    return S;
+}
+
+// first i in [lo, hi) with a[i] >= x (a ascending), or hi
+__device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__ a, uint32_t lo, uint32_t hi, uint32_t x) {
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] < x) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// How a long row is worked on.  Bag-sliced rows (tables whose gradient block is >= 8 sub-slices): every XCD
+// reduces the row's lookups that fall into its bags, sub-slice by sub-slice (one per sweep); rows with at least
+// kHeavyMin lookups are additionally cut into C units per (XCD, sweep) so that all units are of similar size -
+// otherwise the few heaviest rows would keep their workgroups busy long after the others have moved on to later
+// tables, and the XCD's working set would no longer be one sub-slice.  Other long rows: C equal shares.
+constexpr uint32_t kHeavyMin = 8192;
+constexpr uint32_t kUnitLookups = 256;
+struct LongPlan {
+    bool sliced;
+    uint32_t nsub;    // sub-slices per XCD (sweeps that touch the row)
+    uint32_t C;       // units per (XCD, sweep) if sliced, else number of equal shares
+    uint32_t nslots;  // partial sums of the row
+};
+__device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t len) {
+    LongPlan p;
+    const uint32_t S = slices_for(B, D);
+    if (S >= 8u) {
+        p.sliced = true;
+        p.nsub = S / 8u;
+        p.C = len >= kHeavyMin ? len / (8u * p.nsub * kUnitLookups) + 2u : 1u;
+        p.nslots = p.C == 1u ? 8u : 8u * p.nsub * p.C;   // light: one per XCD, summed over the sweeps in place
+    } else {
+        p.sliced = false;
+        p.nsub = 1;
+        p.C = (len + kSegChunk - 1) / kSegChunk;
+        if (p.C > (uint32_t)kMaxParts) p.C = kMaxParts;
+        p.nslots = p.C;
+    }
+    return p;
+}
+
+// ---- 1a/1c. count the long rows of every table, then (FILL) list them grouped by table ----------------
+// long_list entry: (u, first partial slot, C | kSlicedFlag, table).  Order inside a table is arrival order;
+// it only decides where partial sums are parked, never the order in which they are added.
+template <bool FILL>
+__global__ __launch_bounds__(256) void seg_long_list_kernel(const SegArgs a, uint32_t* __restrict__ counters,
+                                                            uint32_t* __restrict__ tcount,
+                                                            const uint32_t* __restrict__ tbase,
+                                                            uint32_t* __restrict__ tfill) {
     const uint32_t U = counters[0];
     const uint32_t stride = gridDim.x * blockDim.x;
     for (uint32_t u = blockIdx.x * blockDim.x + threadIdx.x; u < U; u += stride) {
         const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
-        if (len > (uint32_t)kSegChunk && a.keys_unique[u] < a.total_rows) {
-            const uint32_t nch = (len + kSegChunk - 1) / kSegChunk;
-            const uint32_t li = atomicAdd(&counters[1], 1u);
-            const uint32_t slot = atomicAdd(&counters[2], nch);
-            if (li < a.cap_long && slot + nch <= a.cap_chunks) {  // always true by construction of the capacities
-                a.long_list[3 * li + 0] = u;
-                a.long_list[3 * li + 1] = slot;
-                a.long_list[3 * li + 2] = nch;
-                for (uint32_t k = 0; k < nch; ++k) {
-                    a.chunk_desc[2 * (slot + k) + 0] = u;
-                    a.chunk_desc[2 * (slot + k) + 1] = k;
-                }
+        if (len <= (uint32_t)kSegChunk) continue;
+        const uint32_t key = a.keys_unique[u];
+        if (key >= a.total_rows) continue;
+        const int t = table_of_key(a.row_base, a.T, key);
+        if (!FILL) {
+            atomicAdd(&tcount[t], 1u);
+        } else {
+            const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len);
+            const uint32_t pos = tbase[t] + atomicAdd(&tfill[t], 1u);
+            const uint32_t slot = atomicAdd(&counters[2], p.nslots);
+            if (pos < a.cap_long && slot + p.nslots <= a.cap_chunks) {  // always true: the capacities cover the bound
+                uint4* e = reinterpret_cast<uint4*>(a.long_list) + pos;
+                *e = make_uint4(u, slot, p.C | (p.sliced ? kSlicedFlag : 0u), (uint32_t)t);
+            } else if (pos < a.cap_long) {
+                reinterpret_cast<uint4*>(a.long_list)[pos] = make_uint4(u, 0u, 0u, (uint32_t)t);  // C = 0: no units
             }
         }
     }
 }
 
-// ---- 2. one wavefront per chunk of a long row: partial[slot] = sum of the chunk's gradient slices --
-template <int NC, bool MEAN>
-__global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial_kernel(const SegArgs a) {
-    const uint32_t nchunks = a.counters[2] < a.cap_chunks ? a.counters[2] : a.cap_chunks;
+// ---- 1b. exclusive scan of the per-table counts (one workgroup) ---------------------------------------
+__global__ __launch_bounds__(256) void seg_long_scan_kernel(const uint32_t* __restrict__ tcount, uint32_t* __restrict__ tbase,
+                                                            uint32_t* __restrict__ tfill, const int T,
+                                                            uint32_t* __restrict__ counters) {
+    __shared__ uint32_t smem[256 / kWave];
+    uint32_t carry = 0;
+    for (int base = 0; base < T; base += 256) {
+        const int i = base + threadIdx.x;
+        const uint32_t v = (i < T) ? tcount[i] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<256>(v, smem, &tot);
+        if (i < T) {
+            tbase[i] = carry + ex;
+            tfill[i] = 0u;
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        tbase[T] = carry;
+        counters[1] = carry;  // number of long rows
+    }
+}
+
+// ---- 1d. work units in list (= table) order: unit (pos, c) for c < C(pos); one workgroup -------------
+__global__ __launch_bounds__(1024) void seg_long_units_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+    __shared__ uint32_t smem[1024 / kWave];
+    const uint32_t nlong = counters[1] < a.cap_long ? counters[1] : a.cap_long;
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < nlong; base += 1024) {
+        const uint32_t pos = base + threadIdx.x;
+        const uint32_t C = pos < nlong ? (list[pos].z & ~kSlicedFlag) : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<1024>(C, smem, &tot);
+        for (uint32_t c = 0; c < C; ++c) {
+            const uint32_t e = carry + ex + c;
+            if (e < a.cap_units) a.unit_list[e] = make_uint2(pos, c);
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) counters[3] = carry < a.cap_units ? carry : a.cap_units;  // number of units
+}
+
+// ---- 1e. bag-sliced rows: where each sub-slice starts in the row's segment (one wavefront per row) ------
+// bounds[pos][k] = first sorted position of the row whose bag is >= start of sub-slice k, k = 0 .. S; the
+// sub-slices of XCD x are k = x*nsub .. (x+1)*nsub - 1.
+__global__ __launch_bounds__(kSegThreads) void seg_long_bounds_kernel(const SegArgs a) {
+    const int lane = lane_id();
+    const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
-    for (uint32_t w = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); w < nchunks; w += nwaves) {
-        const uint32_t u = a.chunk_desc[2 * w + 0];
-        const uint32_t k = a.chunk_desc[2 * w + 1];
-        const uint32_t key = a.keys_unique[u];
-        const int t = table_of_key(a.row_base, a.T, key);
-        const int d0 = a.D_off[t];
-        const RowGeom g = row_geom(a.D_off[t + 1] - d0);
-        const uint32_t s = a.seg_start[u] + k * kSegChunk;
-        const uint32_t e_row = a.seg_start[u + 1];
-        const uint32_t e = (s + kSegChunk < e_row) ? s + kSegChunk : e_row;
-        float* dst = a.partial + (size_t)w * a.maxD;
-        float acc[NC][4];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-        segment_reduce<NC, MEAN>(acc, g, a.grad_out + d0, a.sumD, (int64_t)t * a.B, a.bag_sorted, a.offsets, s, e);
-        fold_groups<NC>(acc, g);
-        if (g.sub == 0) {
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int col = g.lc + c * kWave * 4;
-                if (col < g.D) *reinterpret_cast<float4*>(dst + col) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+    const uint32_t W8 = ((uint32_t)a.B + 7u) / 8u;
+    for (uint32_t pos = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); pos < nlong; pos += nwaves) {
+        const uint4 ent = list[pos];
+        if (!(ent.z & kSlicedFlag)) continue;
+        const int t = (int)ent.w;
+        const uint32_t nsub = slices_for((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t])) / 8u;
+        const uint32_t S = 8u * nsub;  // <= 64
+        const uint32_t Wsub = (W8 + nsub - 1) / nsub;
+        const uint32_t s = a.seg_start[ent.x];
+        const uint32_t e = a.seg_start[ent.x + 1];
+        const uint32_t bag0 = (uint32_t)t * (uint32_t)a.B;
+        for (uint32_t k = lane; k <= S; k += kWave) {
+            uint32_t r;
+            if (k == 0) r = s;
+            else if (k == S) r = e;
+            else {
+                const uint32_t x = k / nsub, j = k - x * nsub;
+                uint32_t b_lo = x * W8 + j * Wsub;
+                if (b_lo > (x + 1) * W8) b_lo = (x + 1) * W8;
+                r = lower_bound_u32(a.bag_sorted, s, e, bag0 + b_lo);
             }
+            a.bounds[(size_t)pos * (kMaxSlices + 1) + k] = r;
+        }
+    }
+}
+
+// ---- 2. one workgroup per unit (and XCD); one launch per sweep -----------------------------------------
+// partial[slot] (+)= sum of a range of the row's lookups.  The workgroups of an XCD walk the unit list with a
+// fixed stride, all units being of similar size, so the units in flight on an XCD are neighbours in the list
+// (the hot rows of a few tables); the kernel boundary between sweeps re-aligns them.  A light row's partial sum
+// is accumulated over the sweeps by the same workgroup; the kernel boundary orders those updates.
+// (Handing out units in strict list order through an atomic ticket was tried: device-scope atomics on one
+// address cost more than the better alignment gained.)
+template <int NC, bool MEAN>
+__global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial_kernel(const SegArgs a, const uint32_t sweep) {
+    __shared__ float s_part[kSegThreads / kWave][NC * 256];
+    const uint32_t nunits = a.counters[3];
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
+    const uint32_t xcd = blockIdx.x & 7u;
+    const int wv = threadIdx.x >> 6;
+    {
+        for (uint32_t e = blockIdx.x >> 3; e < nunits; e += gridDim.x >> 3) {
+            const uint2 un = a.unit_list[e];
+            const uint4 ent = list[un.x];
+            const uint32_t C = ent.z & ~kSlicedFlag;
+            const uint32_t c = un.y;
+            const int t = (int)ent.w;
+            const int d0 = a.D_off[t];
+            const RowGeom g = row_geom(a.D_off[t + 1] - d0);
+            uint32_t lo, hi, slot;
+            bool accumulate = false;
+            if (ent.z & kSlicedFlag) {
+                const uint32_t nsub = slices_for((uint32_t)a.B, (uint32_t)g.D) / 8u;
+                if (sweep >= nsub) continue;  // uniform over the workgroup
+                const uint32_t* bd = a.bounds + (size_t)un.x * (kMaxSlices + 1) + xcd * nsub + sweep;
+                const uint32_t r_lo = bd[0], r_hi = bd[1];            // this XCD's lookups of the sub-slice
+                const uint32_t q = (r_hi - r_lo + C - 1) / C;          // ... cut into C units
+                lo = r_lo + c * q < r_hi ? r_lo + c * q : r_hi;
+                hi = lo + q < r_hi ? lo + q : r_hi;
+                if (C == 1u) {
+                    slot = ent.y + xcd;
+                    accumulate = sweep > 0;  // same workgroup as in the earlier sweep: plain read-add-write
+                } else {
+                    slot = ent.y + (xcd * nsub + sweep) * C + c;
+                }
+            } else {
+                if (sweep != 0u || (e & 7u) != xcd) continue;  // uniform over the workgroup; an XCD sees every unit
+                const uint32_t s = a.seg_start[ent.x];
+                const uint64_t len = a.seg_start[ent.x + 1] - s;
+                lo = s + (uint32_t)(len * c / C);
+                hi = s + (uint32_t)(len * (c + 1) / C);
+                slot = ent.y + c;
+            }
+            // the four wavefronts take consecutive quarters (multiples of 64 positions)
+            const uint32_t n = hi - lo;
+            const uint32_t q4 = (((n + 3) / 4) + kWave - 1) / kWave * kWave;
+            const uint32_t ws_ = lo + (uint32_t)wv * q4 < hi ? lo + (uint32_t)wv * q4 : hi;
+            const uint32_t we_ = ws_ + q4 < hi ? ws_ + q4 : hi;
+            float acc[NC][4];
+#pragma unroll
+            for (int cc = 0; cc < NC; ++cc) acc[cc][0] = acc[cc][1] = acc[cc][2] = acc[cc][3] = 0.f;
+            const GradView gv = grad_view(a, t, d0, g.D);
+            segment_reduce<NC, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t * a.B, a.bag_sorted, a.offsets, ws_, we_);
+            fold_groups<NC>(acc, g);
+            if (g.sub == 0) {
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) {
+                    const int col = g.lc + cc * kWave * 4;
+                    if (col < g.D)
+                        *reinterpret_cast<float4*>(&s_part[wv][col]) = make_float4(acc[cc][0], acc[cc][1], acc[cc][2], acc[cc][3]);
+                }
+            }
+            __syncthreads();
+            float* dst = a.partial + (size_t)slot * a.maxD;
+            for (int col = threadIdx.x * 4; col < g.D; col += kSegThreads * 4) {
+                float4 r = accumulate ? *reinterpret_cast<const float4*>(dst + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int w2 = 0; w2 < kSegThreads / kWave; ++w2) {   // fixed order: wavefront 0, 1, 2, 3
+                    const float4 o = *reinterpret_cast<const float4*>(&s_part[w2][col]);
+                    r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
+                }
+                *reinterpret_cast<float4*>(dst + col) = r;
+            }
+            __syncthreads();
         }
     }
 }
@@ -274,7 +527,8 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                 const int t_r = __shfl(t, r, kWave);
                 const float v_r = __shfl(v, r, kWave);
                 float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
-                segment_reduce<1, MEAN>(acc, g, a.grad_out + a.D_off[t_r], a.sumD, (int64_t)t_r * a.B, a.bag_sorted,
+                const GradView gv = grad_view(a, t_r, a.D_off[t_r], g.D);
+                segment_reduce<1, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t_r * a.B, a.bag_sorted,
                                         a.offsets, s_r, s_r + len_r);
                 fold_groups<1>(acc, g);
                 WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
@@ -305,7 +559,8 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             const float gv = __shfl(v, gi, kWave);
             const int goff = (int)(gs - s_r);
             const bool col_on = g.lc < g.D;
-            const float* gcol = a.grad_out + a.D_off[gt] + g.lc;
+            const GradView gvw = grad_view(a, gt, a.D_off[gt], g.D);
+            const float* gcol = gvw.base + g.lc;
             const int64_t bag0 = (int64_t)gt * a.B;
             WT* wrow = tables + a.w_off[gt] + ((int64_t)gkey - a.row_base[gt]) * g.D;
             uint32_t lmax = glen;  // longest row of the round (wave-uniform loop bound)
@@ -324,7 +579,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                     const uint32_t bag = __shfl(my_bag, src, kWave);
                     sc[uu] = MEAN ? __shfl(my_s, src, kWave) : 1.f;
                     const bool on = qi < glen && col_on;
-                    x[uu] = on ? *reinterpret_cast<const float4*>(gcol + ((int64_t)bag - bag0) * a.sumD)
+                    x[uu] = on ? *reinterpret_cast<const float4*>(gcol + ((int64_t)bag - bag0) * gvw.stride)
                                : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
 #pragma unroll
@@ -366,25 +621,29 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         float acc[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-        segment_reduce<4, MEAN>(acc, g, a.grad_out + d0, a.sumD, (int64_t)t * a.B, a.bag_sorted, a.offsets, s, e);
+        const GradView gv = grad_view(a, t, d0, g.D);
+        segment_reduce<4, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t * a.B, a.bag_sorted, a.offsets, s, e);
         fold_groups<4>(acc, g);
         adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], g.sub == 0, a.lr, a.eps, a.inv_c);
     }
 }
 
-// ---- 4. one wavefront per long row: add its chunks' partial sums in chunk order, then step --------
+// ---- 4. one wavefront per long row: add its parts' partial sums in part order, then step ------------
 template <typename WT>
 __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegArgs a) {
     const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     WT* tables = static_cast<WT*>(a.tables);
     for (uint32_t li = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); li < nlong; li += nwaves) {
-        const uint32_t u = a.long_list[3 * li + 0];
-        const uint32_t slot = a.long_list[3 * li + 1];
-        const uint32_t nch = a.long_list[3 * li + 2];
+        const uint4 ent = reinterpret_cast<const uint4*>(a.long_list)[li];
+        const uint32_t u = ent.x;
+        const uint32_t slot = ent.y;
         const uint32_t key = a.keys_unique[u];
-        const int t = table_of_key(a.row_base, a.T, key);
+        const int t = (int)ent.w;
         const int D = a.D_off[t + 1] - a.D_off[t];
+        const uint32_t C = ent.z & ~kSlicedFlag;
+        uint32_t nch = C;  // partial sums of the row, added in slot order
+        if (ent.z & kSlicedFlag) nch = C == 1u ? 8u : C * (slices_for((uint32_t)a.B, (uint32_t)D));
         // here all 64 lanes cover the row (or a 256-column part of it); groups are not used
         RowGeom g;
         g.D = D; g.LPR = kWave; g.G = 1; g.sub = 0; g.lc = lane_id() * 4;
@@ -418,6 +677,14 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[spare]);
     a.offsets = offsets;
     a.grad_out = grad_out;
+    a.grad_tm = nullptr;
+    if (w.grad_tm_bytes) {
+        float* gtm = reinterpret_cast<float*>(ws + w.grad_tm);
+        LaunchTimer tm(h, s, "grad_to_table_major");
+        grad_to_table_major_kernel<<<B, 256, 0, s>>>(grad_out, gtm, h->d_D_off, h->T, B, h->sumD);
+        tm.done();
+        a.grad_tm = gtm;
+    }
     a.D_off = h->d_D_off;
     a.row_base = h->d_row_base;
     a.w_off = h->d_w_off;
@@ -432,26 +699,40 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.tables = tables;
     a.state = state;
     a.long_list = reinterpret_cast<uint32_t*>(ws + w.long_list);
-    a.chunk_desc = reinterpret_cast<uint32_t*>(ws + w.chunk_desc);
     a.partial = reinterpret_cast<float*>(ws + w.partial);
+    a.unit_list = reinterpret_cast<uint2*>(ws + w.unit_list);
+    a.bounds = reinterpret_cast<uint32_t*>(ws + w.bounds);
+    a.cap_units = (uint32_t)w.cap_units;
     a.cap_long = (uint32_t)w.cap_long;
     a.cap_chunks = (uint32_t)w.cap_chunks;
     const bool mean = pooling == TBE_MEAN;
     const bool f32 = h->dtype == TBE_F32;
     const bool narrow = h->maxD <= 256;
+    uint32_t* tcount = reinterpret_cast<uint32_t*>(ws + w.long_tables);
+    uint32_t* tbase = tcount + (h->T + 1);
+    uint32_t* tfill = tbase + (h->T + 1);
     {
-        LaunchTimer tm(h, s, "seg_schedule");
-        seg_schedule_kernel<<<512, 256, 0, s>>>(a, counters);
+        LaunchTimer tm(h, s, "seg_long_list");
+        seg_long_list_kernel<false><<<512, 256, 0, s>>>(a, counters, tcount, tbase, tfill);
+        seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
+        seg_long_list_kernel<true><<<512, 256, 0, s>>>(a, counters, tcount, tbase, tfill);
+        seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
+        if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<256, kSegThreads, 0, s>>>(a);
         tm.done();
     }
     {
         LaunchTimer tm(h, s, "seg_long_partial");
-        if (narrow) {
-            if (mean) seg_long_partial_kernel<1, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            else seg_long_partial_kernel<1, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-        } else {
-            if (mean) seg_long_partial_kernel<4, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            else seg_long_partial_kernel<4, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
+        // one launch per sub-slice of an XCD's bags (as many as the widest table has; at least one for the shares)
+        uint32_t nsweeps = slices_for((uint32_t)B, (uint32_t)h->maxD) / 8u;
+        if (nsweeps < 1u) nsweeps = 1u;
+        for (uint32_t sw = 0; sw < nsweeps; ++sw) {
+            if (narrow) {
+                if (mean) seg_long_partial_kernel<1, true><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sw);
+                else seg_long_partial_kernel<1, false><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sw);
+            } else {
+                if (mean) seg_long_partial_kernel<4, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, sw);
+                else seg_long_partial_kernel<4, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, sw);
+            }
         }
         tm.done();
     }
