@@ -492,8 +492,8 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
     const uint32_t nblk = (U + kWave - 1) / kWave;
-    const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     WT* tables = static_cast<WT*>(a.tables);
+    const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     for (uint32_t blk = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); blk < nblk; blk += nwaves) {
         // ---- one row per lane: bounds, key, table, width, moment
         const uint32_t u = blk * kWave + lane;

@@ -12,7 +12,10 @@ namespace tbe {
 
 // ---- tunables that fix the workspace layout -------------------------------------------------
 constexpr int kSegChunk = 512;         // a unique row with more lookups than this is split into chunks of this size
-constexpr int kRadixTile = 2048;       // elements per radix-sort tile (256 threads x 8)
+#ifndef TBE_RADIX_TILE
+#define TBE_RADIX_TILE 4096
+#endif
+constexpr int kRadixTile = TBE_RADIX_TILE;  // elements per radix-sort tile (256 threads x items per thread)
 constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous slice of the input
 constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile

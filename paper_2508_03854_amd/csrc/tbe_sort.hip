@@ -112,6 +112,21 @@ constexpr int kRsWaves = kRsThreads / kWave;
 constexpr int kRsItems = kRadixTile / kRsThreads;  // 8
 constexpr int kRsBins = 256;
 
+// One digit count into the wavefront's private histogram.  When every active lane holds the same digit (the
+// common case for the high digits, because ids arrive grouped by table) one lane adds the whole count instead of
+// 64 lanes queueing on one LDS word.
+__device__ __forceinline__ void hist_add(uint32_t* __restrict__ hw, const uint32_t d, const bool valid) {
+    const uint64_t act = __ballot(valid);
+    if (act == 0ull) return;
+    const uint32_t d0 = __shfl(d, __ffsll((unsigned long long)act) - 1, kWave);
+    const uint64_t same = __ballot(valid && d == d0);
+    if (same == act) {
+        if (lane_id() == __ffsll((unsigned long long)act) - 1) atomicAdd(&hw[d0], (uint32_t)__popcll(act));
+    } else if (valid) {
+        atomicAdd(&hw[d], 1u);
+    }
+}
+
 __global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* __restrict__ keys, const int64_t N,
                                                                 const int64_t chunk, const int shift,
                                                                 const uint32_t mask, const int nbins, const int G,
@@ -119,12 +134,26 @@ __global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* 
     __shared__ uint32_t h[kRsWaves][kRsBins];
     for (int i = threadIdx.x; i < kRsWaves * kRsBins; i += kRsThreads) (&h[0][0])[i] = 0u;
     __syncthreads();
-    const int w = threadIdx.x >> 6;
-    const int64_t s = (int64_t)blockIdx.x * chunk;
+    uint32_t* hw = h[threadIdx.x >> 6];
+    const int64_t s = (int64_t)blockIdx.x * chunk;  // multiple of 2048 elements: 16-byte aligned
     const int64_t e = (s + chunk < N) ? s + chunk : N;
-    for (int64_t i = s + threadIdx.x; i < e; i += kRsThreads) {
-        const uint32_t d = (keys[i] >> shift) & mask;
-        atomicAdd(&h[w][d], 1u);
+    const int64_t n4 = e > s ? (e - s) >> 2 : 0;    // whole uint4 groups
+    const uint4* k4 = reinterpret_cast<const uint4*>(keys + s);
+    for (int64_t base = 0; base < n4; base += kRsThreads) {
+        const int64_t i = base + threadIdx.x;
+        const bool valid = i < n4;
+        uint4 k = make_uint4(0u, 0u, 0u, 0u);
+        if (valid) k = k4[i];
+        hist_add(hw, (k.x >> shift) & mask, valid);
+        hist_add(hw, (k.y >> shift) & mask, valid);
+        hist_add(hw, (k.z >> shift) & mask, valid);
+        hist_add(hw, (k.w >> shift) & mask, valid);
+    }
+    {   // up to 3 trailing elements
+        const int64_t i = s + 4 * n4 + threadIdx.x;
+        const bool valid = i < e;
+        const uint32_t k = valid ? keys[i] : 0u;
+        hist_add(hw, (k >> shift) & mask, valid);
     }
     __syncthreads();
     for (int d = threadIdx.x; d < nbins; d += kRsThreads) {
@@ -349,6 +378,7 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
 __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys,
                                                                 const uint32_t* __restrict__ vals,
                                                                 const uint32_t* __restrict__ bag_of_pos, const int64_t N,
+                                                                const int ntiles,
                                                                 const uint32_t* __restrict__ block_base,
                                                                 uint32_t* __restrict__ unique_rows,
                                                                 uint32_t* __restrict__ seg_start,
@@ -357,12 +387,27 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
     const int lane = lane_id();
     const int w = threadIdx.x >> 6;
     const uint64_t lt = lanemask_lt();
-    const int64_t base = (int64_t)blockIdx.x * kRleTile;
+    // XCD-aware tile order: workgroup w runs on XCD w % 8; giving every XCD one contiguous eighth of the sorted
+    // sequence keeps the positions it resolves inside one or two tables, i.e. a bag_of_pos window that its L2 holds.
+    const uint32_t per_xcd = (gridDim.x + 7u) / 8u;
+    const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= (uint32_t)ntiles) return;
+    const int64_t base = (int64_t)tile * kRleTile;
     uint64_t heads[kRleItems];
+    {   // all positions first, then all dependent gathers, then the stores: 8 independent chains in flight
+        uint32_t pv[kRleItems], bg[kRleItems];
 #pragma unroll
-    for (int k = 0; k < kRleItems; ++k) {
-        const int64_t i = base + k * kRleThreads + threadIdx.x;
-        if (i < N) bag_sorted[i] = bag_of_pos[vals[i]];
+        for (int k = 0; k < kRleItems; ++k) {
+            const int64_t i = base + k * kRleThreads + threadIdx.x;
+            pv[k] = i < N ? vals[i] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kRleItems; ++k) bg[k] = bag_of_pos[pv[k]];   // pv is a valid position (0 for the tail)
+#pragma unroll
+        for (int k = 0; k < kRleItems; ++k) {
+            const int64_t i = base + k * kRleThreads + threadIdx.x;
+            if (i < N) bag_sorted[i] = bg[k];
+        }
     }
 #pragma unroll
     for (int k = 0; k < kRleItems; ++k) {
@@ -376,7 +421,7 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
         if (threadIdx.x < kRleRuns) s_run[threadIdx.x] = inc - v;
     }
     __syncthreads();
-    const uint32_t bb = block_base[blockIdx.x];
+    const uint32_t bb = block_base[tile];
 #pragma unroll
     for (int k = 0; k < kRleItems; ++k) {
         if ((heads[k] >> lane) & 1ull) {
@@ -410,8 +455,9 @@ hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws,
     }
     {
         LaunchTimer tm(h, s, "rle_write");
-        rle_write_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, vals_sorted, bag_of_pos, N, counts, unique_rows,
-                                                              seg_start, bag_sorted);
+        const int grid = (w.rle_blocks + 7) / 8 * 8;  // whole rounds over the 8 XCDs
+        rle_write_kernel<<<grid, kRleThreads, 0, s>>>(keys_sorted, vals_sorted, bag_of_pos, N, w.rle_blocks, counts,
+                                                      unique_rows, seg_start, bag_sorted);
         tm.done();
     }
     return hipGetLastError();
