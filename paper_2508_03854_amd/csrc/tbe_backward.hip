@@ -74,6 +74,8 @@ struct SegArgs {
     float* state;
     uint32_t* long_list;   // [cap_long][4]  (u, first slot, parts | sliced flag, table)
     float* partial;        // [cap_chunks][maxD] partial sums of long rows
+    uint2* raw_long;       // [cap_long] long rows in arrival order (u, table), written by the row-update kernel
+    uint32_t* tcount;      // [T+1] long rows per table (then tbase [T+1], tfill [T+1] behind it)
     uint2* unit_list;      // [cap_units] (position in long_list, unit index)
     uint32_t* bounds;      // [cap_long][kMaxSlices + 1] sub-slice borders inside a sliced row's segment
     uint32_t cap_units;
@@ -269,8 +271,14 @@ __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__
 // kHeavyMin lookups are additionally cut into C units per (XCD, sweep) so that all units are of similar size -
 // otherwise the few heaviest rows would keep their workgroups busy long after the others have moved on to later
 // tables, and the XCD's working set would no longer be one sub-slice.  Other long rows: C equal shares.
-constexpr uint32_t kHeavyMin = 8192;
-constexpr uint32_t kUnitLookups = 256;
+#ifndef TBE_HEAVY_MIN
+#define TBE_HEAVY_MIN 8192
+#endif
+#ifndef TBE_UNIT_LOOKUPS
+#define TBE_UNIT_LOOKUPS 256
+#endif
+constexpr uint32_t kHeavyMin = TBE_HEAVY_MIN;
+constexpr uint32_t kUnitLookups = TBE_UNIT_LOOKUPS;
 struct LongPlan {
     bool sliced;
     uint32_t nsub;    // sub-slices per XCD (sweeps that touch the row)
@@ -295,35 +303,34 @@ __device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t l
     return p;
 }
 
-// ---- 1a/1c. count the long rows of every table, then (FILL) list them grouped by table ----------------
+// Called by the row-update kernels for a row they leave to the long-row path: remember it, and count it for its table.
+__device__ __forceinline__ void note_long_row(const SegArgs& a, uint32_t* counters, uint32_t u, uint32_t key) {
+    const int t = table_of_key(a.row_base, a.T, key);
+    atomicAdd(&a.tcount[t], 1u);
+    const uint32_t pos = atomicAdd(&counters[4], 1u);
+    if (pos < a.cap_long) a.raw_long[pos] = make_uint2(u, (uint32_t)t);
+}
+
+// ---- 1a. the long rows, grouped by table --------------------------------------------------------------
 // long_list entry: (u, first partial slot, C | kSlicedFlag, table).  Order inside a table is arrival order;
 // it only decides where partial sums are parked, never the order in which they are added.
-template <bool FILL>
-__global__ __launch_bounds__(256) void seg_long_list_kernel(const SegArgs a, uint32_t* __restrict__ counters,
-                                                            uint32_t* __restrict__ tcount,
+__global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, uint32_t* __restrict__ counters,
                                                             const uint32_t* __restrict__ tbase,
                                                             uint32_t* __restrict__ tfill) {
-    const uint32_t U = counters[0];
+    const uint32_t n = counters[4] < a.cap_long ? counters[4] : a.cap_long;
     const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t u = blockIdx.x * blockDim.x + threadIdx.x; u < U; u += stride) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint2 rl = a.raw_long[i];
+        const uint32_t u = rl.x;
+        const int t = (int)rl.y;
         const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
-        if (len <= (uint32_t)kSegChunk) continue;
-        const uint32_t key = a.keys_unique[u];
-        if (key >= a.total_rows) continue;
-        const int t = table_of_key(a.row_base, a.T, key);
-        if (!FILL) {
-            atomicAdd(&tcount[t], 1u);
-        } else {
-            const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len);
-            const uint32_t pos = tbase[t] + atomicAdd(&tfill[t], 1u);
-            const uint32_t slot = atomicAdd(&counters[2], p.nslots);
-            if (pos < a.cap_long && slot + p.nslots <= a.cap_chunks) {  // always true: the capacities cover the bound
-                uint4* e = reinterpret_cast<uint4*>(a.long_list) + pos;
-                *e = make_uint4(u, slot, p.C | (p.sliced ? kSlicedFlag : 0u), (uint32_t)t);
-            } else if (pos < a.cap_long) {
-                reinterpret_cast<uint4*>(a.long_list)[pos] = make_uint4(u, 0u, 0u, (uint32_t)t);  // C = 0: no units
-            }
-        }
+        const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len);
+        const uint32_t pos = tbase[t] + atomicAdd(&tfill[t], 1u);
+        const uint32_t slot = atomicAdd(&counters[2], p.nslots);
+        if (pos >= a.cap_long) continue;  // never true: at most n/(kSegChunk+1) rows are long
+        uint4* e = reinterpret_cast<uint4*>(a.long_list) + pos;
+        if (slot + p.nslots <= a.cap_chunks) *e = make_uint4(u, slot, p.C | (p.sliced ? kSlicedFlag : 0u), (uint32_t)t);
+        else *e = make_uint4(u, 0u, 0u, (uint32_t)t);  // never true: the capacity covers the bound; C = 0: no units
     }
 }
 
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
 
 // ---- 3a. rows with at most kSegChunk lookups, all tables at most 256 columns wide ------------------
 template <typename WT, bool MEAN>
-__global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArgs a) {
+__global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
     const uint32_t nblk = (U + kWave - 1) / kWave;
@@ -505,6 +512,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
         }
         const uint32_t len = e - s;
         const bool live = (u < U) && len >= 1 && len <= (uint32_t)kSegChunk && key < a.total_rows;
+        if ((u < U) && len > (uint32_t)kSegChunk && key < a.total_rows) note_long_row(a, counters, u, key);
         int t = 0, D = 4;
         float v = 0.f;
         if (live) {
@@ -605,7 +613,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
 
 // ---- 3b. same rows, any width up to 1024 columns: one wavefront per row ----------------------------
 template <typename WT, bool MEAN>
-__global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const SegArgs a) {
+__global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     const uint32_t U = a.counters[0];
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     WT* tables = static_cast<WT*>(a.tables);
@@ -613,7 +621,11 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         const uint32_t s = a.seg_start[u];
         const uint32_t e = a.seg_start[u + 1];
         const uint32_t key = a.keys_unique[u];
-        if (e - s > (uint32_t)kSegChunk || key >= a.total_rows) continue;  // long rows: kernel 4; invalid ids: no row
+        if (key >= a.total_rows) continue;  // invalid ids: no row
+        if (e - s > (uint32_t)kSegChunk) {   // long rows are left to the long-row kernels
+            if (lane_id() == 0) note_long_row(a, counters, u, key);
+            continue;
+        }
         const int t = table_of_key(a.row_base, a.T, key);
         const int d0 = a.D_off[t];
         const RowGeom g = row_geom(a.D_off[t + 1] - d0);
@@ -628,13 +640,16 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
     }
 }
 
-// ---- 4. one wavefront per long row: add its parts' partial sums in part order, then step ------------
+// ---- 4. one workgroup per long row: add its partial sums, then the step ----------------------------------
+// Wavefront w adds slots w, w+4, ... in ascending order, the four sums are added in wavefront order, and
+// wavefront 0 applies the step: a fixed order, so the result does not depend on scheduling.
 template <typename WT>
 __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegArgs a) {
+    __shared__ float s_sum[kSegThreads / kWave][1024];
     const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
-    const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     WT* tables = static_cast<WT*>(a.tables);
-    for (uint32_t li = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); li < nlong; li += nwaves) {
+    const int wv = threadIdx.x >> 6;
+    for (uint32_t li = blockIdx.x; li < nlong; li += gridDim.x) {
         const uint4 ent = reinterpret_cast<const uint4*>(a.long_list)[li];
         const uint32_t u = ent.x;
         const uint32_t slot = ent.y;
@@ -642,16 +657,15 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
         const int t = (int)ent.w;
         const int D = a.D_off[t + 1] - a.D_off[t];
         const uint32_t C = ent.z & ~kSlicedFlag;
-        uint32_t nch = C;  // partial sums of the row, added in slot order
+        uint32_t nch = C;  // partial sums of the row
         if (ent.z & kSlicedFlag) nch = C == 1u ? 8u : C * (slices_for((uint32_t)a.B, (uint32_t)D));
         // here all 64 lanes cover the row (or a 256-column part of it); groups are not used
         RowGeom g;
         g.D = D; g.LPR = kWave; g.G = 1; g.sub = 0; g.lc = lane_id() * 4;
-        WT* wrow = tables + a.w_off[t] + ((int64_t)key - a.row_base[t]) * D;
         float acc[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-        for (uint32_t k = 0; k < nch; ++k) {
+        for (uint32_t k = (uint32_t)wv; k < nch; k += kSegThreads / kWave) {
             const float* src = a.partial + (size_t)(slot + k) * a.maxD;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -662,7 +676,28 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
                 }
             }
         }
-        adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], true, a.lr, a.eps, a.inv_c);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int col = g.lc + c * 256;
+            if (col < D) *reinterpret_cast<float4*>(&s_sum[wv][col]) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+        }
+        __syncthreads();
+        if (wv == 0) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int col = g.lc + c * 256;
+                if (col < D) {
+#pragma unroll
+                    for (int w2 = 1; w2 < kSegThreads / kWave; ++w2) {
+                        const float4 o = *reinterpret_cast<const float4*>(&s_sum[w2][col]);
+                        acc[c][0] += o.x; acc[c][1] += o.y; acc[c][2] += o.z; acc[c][3] += o.w;
+                    }
+                }
+            }
+            WT* wrow = tables + a.w_off[t] + ((int64_t)key - a.row_base[t]) * D;
+            adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], true, a.lr, a.eps, a.inv_c);
+        }
+        __syncthreads();
     }
 }
 
@@ -711,11 +746,33 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     uint32_t* tcount = reinterpret_cast<uint32_t*>(ws + w.long_tables);
     uint32_t* tbase = tcount + (h->T + 1);
     uint32_t* tfill = tbase + (h->T + 1);
+    a.tcount = tcount;
+    a.raw_long = reinterpret_cast<uint2*>(ws + w.raw_long);
+    {   // rows with at most kSegChunk lookups; the others are noted for the long-row path
+        LaunchTimer tm(h, s, "seg_update");
+        if (narrow) {
+            if (f32) {
+                if (mean) seg_update_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            } else {
+                if (mean) seg_update_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            }
+        } else {
+            if (f32) {
+                if (mean) seg_update_wide_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_wide_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            } else {
+                if (mean) seg_update_wide_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_wide_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            }
+        }
+        tm.done();
+    }
     {
         LaunchTimer tm(h, s, "seg_long_list");
-        seg_long_list_kernel<false><<<512, 256, 0, s>>>(a, counters, tcount, tbase, tfill);
         seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
-        seg_long_list_kernel<true><<<512, 256, 0, s>>>(a, counters, tcount, tbase, tfill);
+        seg_long_fill_kernel<<<64, 256, 0, s>>>(a, counters, tbase, tfill);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
         if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<256, kSegThreads, 0, s>>>(a);
         tm.done();
@@ -737,30 +794,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         tm.done();
     }
     {
-        LaunchTimer tm(h, s, "seg_update");
-        if (narrow) {
-            if (f32) {
-                if (mean) seg_update_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-                else seg_update_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            } else {
-                if (mean) seg_update_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-                else seg_update_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            }
-        } else {
-            if (f32) {
-                if (mean) seg_update_wide_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-                else seg_update_wide_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            } else {
-                if (mean) seg_update_wide_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-                else seg_update_wide_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a);
-            }
-        }
-        tm.done();
-    }
-    {
         LaunchTimer tm(h, s, "seg_long_update");
-        if (f32) seg_long_update_kernel<float><<<256, kSegThreads, 0, s>>>(a);
-        else seg_long_update_kernel<__half><<<256, kSegThreads, 0, s>>>(a);
+        if (f32) seg_long_update_kernel<float><<<512, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<__half><<<512, kSegThreads, 0, s>>>(a);
         tm.done();
     }
     return hipGetLastError();
