@@ -24,7 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
 # known size); see the profile summaries under profiles/.  None = not measured for that workload/kernel.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per launch
+    ("C4", "seg_update"): 131.70e9,
+    ("C4", "forward_pool"): 40.59e9,
+    ("C4", "seg_long_partial"): 4 * 16.62e9,   # four launches (one per sub-slice sweep) under one timing record
+}
 
 
 def profiler_region(resume: bool) -> None:
@@ -71,7 +76,7 @@ def algorithmic_bytes(cfg, nnz, U_t):
         "seg_long_list": U * 8,
         # gradient once, sorted positions and their bags, row + moment read-modify-write per unique row
         "seg_update": dense + nnz * 8 + U * 8 + 2 * rows_bytes + 8 * U,
-        "seg_long_partial": 0,
+        "seg_long_partial": dense,                                  # the hot rows touch (nearly) every bag once more
         "seg_long_update": 0,
     }
 

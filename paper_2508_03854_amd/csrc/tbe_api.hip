@@ -232,7 +232,6 @@ tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_o
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = launch_linearize(h, indices, offsets, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
-                                    reinterpret_cast<uint32_t*>(ws + w.vals[0]),
                                     reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
     if (e != hipSuccess) return TBE_EHIP;
     int buf = 0;

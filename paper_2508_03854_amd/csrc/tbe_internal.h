@@ -81,8 +81,9 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
                           const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
                           hipStream_t s);
 hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
-                            uint32_t* keys, uint32_t* vals, uint32_t* bag_of_pos, hipStream_t s);
-// sorts (keys[0], vals[0]) of the workspace; returns in *result_buf which buffer (0/1) holds the result
+                            uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s);
+// sorts keys[0] of the workspace with the positions 0..N-1 as payload; returns in *result_buf which buffer pair
+// (0/1) holds the sorted keys and positions
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
 // `sorted` is the buffer index (0/1) that holds the sorted (key, position) pairs; the other pair is overwritten
 hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);

@@ -6,7 +6,8 @@
 namespace tbe {
 
 // =================================================================================================
-// linearize: key[p] = row_base[t(p)] + indices[p], val[p] = p, bag_of_pos[p] = linear bag id of p
+// linearize: key[p] = row_base[t(p)] + indices[p], bag_of_pos[p] = linear bag id of p
+// (the sort payload of position p is p itself; the first radix pass generates it instead of reading it)
 // =================================================================================================
 constexpr int kLinThreads = 256;
 
@@ -28,7 +29,7 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const int64_t* _
                                                                 const int64_t nbags, const int32_t B,
                                                                 const int64_t* __restrict__ row_base,
                                                                 const uint32_t invalid_key, const int64_t N,
-                                                                uint32_t* __restrict__ keys, uint32_t* __restrict__ vals,
+                                                                uint32_t* __restrict__ keys,
                                                                 uint32_t* __restrict__ bag_of_pos, int32_t* err) {
     __shared__ int32_t s_off[kLinTile + 2];
     __shared__ int64_t s_lo, s_hi;
@@ -83,19 +84,18 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const int64_t* _
             key = invalid_key;
             atomicOr(err, 1);
         }
-        keys[p] = key;
-        vals[p] = (uint32_t)p;
+        keys[p] = key;                  // the payload of position p is p itself: the first sort pass generates it
         bag_of_pos[p] = (uint32_t)bag;
     }
 }
 
 hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
-                            uint32_t* keys, uint32_t* vals, uint32_t* bag_of_pos, hipStream_t s) {
+                            uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s) {
     const int64_t nbags = (int64_t)h->T * B;
     const unsigned grid = (unsigned)((N + kLinTile - 1) / kLinTile);
     LaunchTimer tm(h, s, "linearize");
     linearize_kernel<<<grid, kLinThreads, 0, s>>>(indices, offsets, nbags, B, h->d_row_base, (uint32_t)h->total_rows, N,
-                                                  keys, vals, bag_of_pos, h->d_err);
+                                                  keys, bag_of_pos, h->d_err);
     tm.done();
     return hipGetLastError();
 }
@@ -188,7 +188,8 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
                                                                    const int64_t chunk, const int shift,
                                                                    const uint32_t mask, const int nbins, const int G,
                                                                    const uint32_t* __restrict__ ghist,
-                                                                   const uint32_t* __restrict__ bin_tot) {
+                                                                   const uint32_t* __restrict__ bin_tot,
+                                                                   const bool iota_vals) {
     __shared__ uint32_t s_cnt[kRsWaves][kRsBins];  // per-wave digit counts, then per-wave exclusive offsets
     __shared__ uint32_t s_base[kRsBins];           // where this block's next element of digit d goes
     __shared__ uint32_t s_dstart[kRsBins];         // start of digit d inside the locally sorted tile
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
             const int64_t i = wbase + k * kWave + lane;
             const bool valid = i < e;
             key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
-            val[k] = valid ? vals_in[i] : 0u;
+            val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // first pass: payload = position
         }
         // rank inside the wave, item by item in input order: peers = valid lanes holding the same digit
 #pragma unroll
@@ -312,7 +313,7 @@ hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, 
         {
             LaunchTimer tm(h, s, "radix_scatter");
             radix_scatter_kernel<<<G, kRsThreads, 0, s>>>(kin, vin, kout, vout, N, w.radix_chunk, shift, mask, nbins, G,
-                                                          ghist, bin_tot);
+                                                          ghist, bin_tot, p == 0);
             tm.done();
         }
         cur ^= 1;
