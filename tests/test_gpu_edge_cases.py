@@ -279,3 +279,39 @@ def test_checkpoint_resume_is_bit_identical():
                 state = state.cpu().cuda()
         res.append((flat.clone(), state.clone()))
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+def test_hand_worked_rows_of_algorithm_1_on_the_gpu():
+    # the fixture's rows (worked by hand from Algorithm 1, steps 5-6), padded with zero columns to the minimum width 4
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import os
+    from paper_2508_03854_amd import TBE
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "algorithm1_worked_rows.txt")
+    n = 0
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        scal, g, w0, v_new, w_new = [np.array(p.split(), dtype=np.float64) for p in line.split("|")]
+        eta, eps, c, v_old = scal
+        pad = lambda x: np.concatenate([x, np.zeros(4 - len(x))]) if len(x) < 4 else x
+        g, w0, w_new = pad(g), pad(w0), pad(w_new)
+        for dtype, tdt in (("f32", torch.float32),):
+            tbe = TBE([3], [4], dtype)
+            flat = torch.tensor(np.stack([w0, w0, w0]).reshape(-1), dtype=tdt, device="cuda")
+            state = torch.tensor([7.0, float(v_old), 7.0], device="cuda")
+            idx = torch.tensor([1], dtype=torch.int64, device="cuda")
+            off = torch.tensor([0, 1], dtype=torch.int64, device="cuda")
+            gout = torch.tensor(g[None, :], dtype=torch.float32, device="cuda")
+            ws = tbe.alloc_workspace(1, 1)
+            tbe.backward_rowwise_adagrad(gout, idx, off, 1, flat, state, ws, lr=float(eta), eps=float(eps),
+                                         momentum_scale=float(c))
+            torch.cuda.synchronize()
+            got = flat.cpu().numpy().reshape(3, 4)
+            np.testing.assert_allclose(got[1], w_new, rtol=1e-6, atol=1e-7)
+            assert np.array_equal(got[0], w0.astype(np.float32)) and np.array_equal(got[2], w0.astype(np.float32))
+            assert state.cpu().tolist() == [7.0, float(v_new[0]), 7.0]
+            tbe.close()
+        n += 1
+    assert n == 5
