@@ -498,12 +498,16 @@ template <typename WT, bool MEAN>
 __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
-    const uint32_t nblk = (U + kWave - 1) / kWave;
-    WT* tables = static_cast<WT*>(a.tables);
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
+    // rows per wavefront pass: 64 when there is plenty of work, fewer when the batch touches so few rows that
+    // whole wavefronts would otherwise go idle while others walk 64 rows one round after the other
+    uint32_t rpw = kWave;
+    while (rpw > 8u && U / rpw < 2u * nwaves) rpw >>= 1;
+    const uint32_t nblk = (U + rpw - 1) / rpw;
+    WT* tables = static_cast<WT*>(a.tables);
     for (uint32_t blk = blockIdx.x * (kSegThreads / kWave) + (threadIdx.x >> 6); blk < nblk; blk += nwaves) {
         // ---- one row per lane: bounds, key, table, width, moment
-        const uint32_t u = blk * kWave + lane;
+        const uint32_t u = (uint32_t)lane < rpw ? blk * rpw + lane : U;
         uint32_t s = 0, e = 0, key = 0;
         if (u < U) {
             s = a.seg_start[u];
@@ -521,7 +525,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             v = a.state[key];
         }
         int r = 0;
-        while (r < kWave) {
+        while (r < (int)rpw) {
             if (!__shfl((int)live, r, kWave)) {
                 ++r;
                 continue;
