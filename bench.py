@@ -56,17 +56,17 @@ def realised_unique(cfg, batches, torch):
     return out
 
 
-def algorithmic_bytes(cfg, nnz, U_t):
+def algorithmic_bytes(cfg, nnz, U_t, ib=8, eb=4):
     """Compulsory bytes of each kernel for one batch: every distinct row once, every index once, the pooled
     output / upstream gradient once, row and moment read-modify-write once per unique row."""
     wb = 4 if cfg.weight_dtype == "f32" else 2
     nb = cfg.T * cfg.B + 1
     rows_bytes = sum(u * d * wb for u, d in zip(U_t, cfg.D))
     U = sum(U_t)
-    dense = cfg.B * cfg.sum_D * 4
+    dense = cfg.B * cfg.sum_D * eb      # eb bytes per element of out / grad_out, ib bytes per id and offset
     return {
-        "forward_pool": rows_bytes + nnz * 8 + nb * 8 + dense,
-        "linearize": nnz * 8 + nb * 8 + nnz * 12,                  # ids + offsets in; key, position, bag out
+        "forward_pool": rows_bytes + nnz * ib + nb * ib + dense,
+        "linearize": nnz * ib + nb * ib + nnz * 12,                # ids + offsets in; key, position, bag out
         "radix_hist": nnz * 4,
         "radix_scatter": nnz * 16,                                  # (key, position) in and out
         "radix_binscan": 0,
@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-scale", type=float, default=1.0,
                     help="shrink every table's row count (profiling aid only; the result is then NOT the named workload)")
+    ap.add_argument("--index-dtype", choices=["i64", "i32"], default="i64", help="ids and offsets (i32: *_ex calls)")
+    ap.add_argument("--io", choices=["f32", "f16", "bf16"], default="f32",
+                    help="element type of out and grad_out (16-bit: *_ex calls)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -118,10 +121,14 @@ def main():
     state = torch.zeros(cfg.total_rows, dtype=torch.float32, device=dev)
     pool = max(1, args.pool)
     batches = W.make_batches(cfg, list(range(pool)), device=dev)
+    extended = args.index_dtype != "i64" or args.io != "f32"
+    io_t = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.io]
+    if args.index_dtype == "i32":
+        batches = [(i.to(torch.int32), o.to(torch.int32)) for i, o in batches]
     log("batches drawn")
     n_go = pool if cfg.B * cfg.sum_D * 4 * pool < 16e9 else 2
-    gouts = [W.make_grad_out(cfg, k, device=dev) for k in range(n_go)]
-    out = torch.empty(cfg.B, cfg.sum_D, dtype=torch.float32, device=dev)
+    gouts = [W.make_grad_out(cfg, k, device=dev).to(io_t) for k in range(n_go)]
+    out = torch.empty(cfg.B, cfg.sum_D, dtype=io_t, device=dev)
     max_nnz = max(int(i.numel()) for i, _ in batches)
     tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
     ws = tbe.alloc_workspace(cfg.B, max_nnz)
@@ -130,6 +137,11 @@ def main():
 
     def step(k):
         idx, off = batches[k % pool]
+        if extended:
+            tbe.forward_ex(flat, idx, off, cfg.B, cfg.pooling, out=out)
+            tbe.backward_rowwise_adagrad_ex(gouts[k % n_go], idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling,
+                                            lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
+            return
         tbe.forward(flat, idx, off, cfg.B, cfg.pooling, out=out)
         tbe.backward_rowwise_adagrad(gouts[k % n_go], idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr,
                                      eps=cfg.eps, momentum_scale=cfg.c)
@@ -178,7 +190,8 @@ def main():
     used = [(args.warmup + args.steps + k) % pool for k in range(prof_steps)]
     alg = {}
     for k in used:
-        for name, b in algorithmic_bytes(cfg, nnz_all[k], U_all[k]).items():
+        for name, b in algorithmic_bytes(cfg, nnz_all[k], U_all[k], ib=8 if args.index_dtype == "i64" else 4,
+                                         eb=4 if args.io == "f32" else 2).items():
             alg[name] = alg.get(name, 0.0) + b / len(used)   # mean over the profiled batches, per step
     kernels = {}
     for name, d in per_kernel.items():
@@ -193,12 +206,12 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": dk["alg_GBps"] / HBM_PEAK_GBPS, "avg_launch_ms": dk["avg_ms"],
                 "alg_bytes_per_launch": dk["alg_bytes_per_launch"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))}
+                "traffic": None if extended else MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))}
     fwd_ms = kernels.get("forward_pool", {}).get("ms_per_step", 0.0)
     kernel_ms = sum(k["ms_per_step"] for k in kernels.values())
     step_alg_bytes = sum(alg.get(n, 0.0) * kernels[n]["launches_per_step"] for n in kernels)
     # compulsory bytes of one whole step: the forward set + the backward set (ids are read once more by linearize)
-    compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * 8
+    compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * (8 if args.index_dtype == "i64" else 4)
 
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1): whole tables, full batch size,
     #      as many leading tables as fit the time budget
@@ -219,7 +232,8 @@ def main():
             i_np = idx[:bounds[nt]].cpu().numpy()
             o_np = off[: nt * cfg.B + 1].cpu().numpy()
             doff = cfg.D_offsets()[nt]
-            g_np = np.ascontiguousarray(gouts[0][:, :doff].cpu().numpy())
+            g_t = gouts[0][:, :doff].contiguous().cpu()
+            g_np = g_t.view(torch.int16).numpy().view(np.uint16) if args.io == "bf16" else g_t.numpy()
             st = np.ascontiguousarray(state[: cfg.row_base()[nt]].cpu().numpy())
             return tabs, st, g_np, i_np, o_np
 
@@ -227,9 +241,9 @@ def main():
             tabs, st, g_np, i_np, o_np = sample(nt)
             t0 = time.perf_counter()
             for _ in range(reps):
-                oracle.forward(tabs, i_np, o_np, cfg.B, cfg.pooling)
+                oracle.forward(tabs, i_np, o_np, cfg.B, cfg.pooling, out_dtype=args.io)
                 oracle.backward_rowwise_adagrad(tabs, st, g_np, i_np, o_np, cfg.B, cfg.pooling, cfg.lr, cfg.eps, cfg.c,
-                                                want_indices=False)
+                                                want_indices=False, grad_dtype=args.io)
             return time.perf_counter() - t0, int(i_np.size) * reps
 
         t1, n1 = run(1, 1)
@@ -255,7 +269,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": (f"{cfg.name}: " if args.rows_scale == 1.0 else f"{cfg.name} with rows x{args.rows_scale}: ")
-                   + W.describe(cfg), "weight_dtype": cfg.weight_dtype,
+                   + W.describe(cfg), "weight_dtype": cfg.weight_dtype, "index_dtype": args.index_dtype,
+                   "io_dtype": args.io,
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
                    "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c},

@@ -53,6 +53,8 @@ typedef enum {
 
 typedef enum { TBE_F32 = 0, TBE_F16 = 1 } tbe_dtype;    /* storage type of the tables; math is fp32 */
 typedef enum { TBE_SUM = 0, TBE_MEAN = 1 } tbe_pooling; /* mean divides a bag's sum by its length */
+typedef enum { TBE_I64 = 0, TBE_I32 = 1 } tbe_index_dtype;                   /* type of indices AND offsets */
+typedef enum { TBE_IO_F32 = 0, TBE_IO_F16 = 1, TBE_IO_BF16 = 2 } tbe_io_dtype; /* pooled output / upstream gradient */
 
 /* Describe the table set.  rows, D: HOST arrays of T entries.  Builds D_offsets / row_base / table
  * offsets on the current device.  The handle can be used by one stream at a time. */
@@ -92,6 +94,21 @@ tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_o
                                         const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
                                         float eps, float momentum_scale, void* tables, float* state, void* workspace,
                                         size_t workspace_bytes, void* hip_stream);
+
+/* Variants with narrower streams (the id, output and gradient streams are the dominant compulsory bytes when
+ * few distinct rows are touched).  Same operations as the two calls above, which are the (TBE_I64, TBE_IO_F32)
+ * case.  index_dtype gives the element type of BOTH indices and offsets (int32 needs nnz < 2^31).  out_dtype /
+ * grad_dtype give the element type of the [B, sum(D)] matrix: float, IEEE binary16 or bfloat16.  Arithmetic is
+ * unchanged (fp32 accumulation): the forward rounds each pooled value once, to nearest even, when it stores it;
+ * the backward converts each gradient element exactly to fp32 when it loads it. */
+tbe_status tbe_forward_ex(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const void* indices,
+                          const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
+                          void* out, tbe_io_dtype out_dtype, void* hip_stream);
+tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                           const void* indices, const void* offsets, tbe_index_dtype index_dtype,
+                                           int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
+                                           float momentum_scale, void* tables, float* state, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
 
 /* Parity hooks: DEVICE pointers into `workspace` holding the integer by-products of the last backward
  * call made with the same (h, workspace, B, nnz); valid until the next backward on that workspace.

@@ -19,6 +19,8 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 F32, F16 = 0, 1
 SUM, MEAN = 0, 1
+IO_F32, IO_F16, IO_BF16 = 0, 1, 2     # element type of the pooled output / upstream gradient matrix
+_IO = {"f32": IO_F32, "f16": IO_F16, "bf16": IO_BF16}
 
 
 def build(force: bool = False) -> str:
@@ -43,6 +45,18 @@ def lib():
         L.oracle_half_to_double.argtypes = [ctypes.c_uint16]
         L.oracle_double_to_half.restype = ctypes.c_uint16
         L.oracle_double_to_half.argtypes = [ctypes.c_double]
+        L.oracle_bf16_to_double.restype = ctypes.c_double
+        L.oracle_bf16_to_double.argtypes = [ctypes.c_uint16]
+        L.oracle_double_to_bf16.restype = ctypes.c_uint16
+        L.oracle_double_to_bf16.argtypes = [ctypes.c_double]
+        L.oracle_forward_io.restype = ctypes.c_int
+        L.oracle_forward_io.argtypes = [ctypes.c_int32, i64p, i32p, ctypes.c_int, vpp, i64p, i64p, ctypes.c_int32,
+                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_int]
+        L.oracle_backward_rowwise_adagrad_io.restype = ctypes.c_int64
+        L.oracle_backward_rowwise_adagrad_io.argtypes = [ctypes.c_int32, i64p, i32p, ctypes.c_int, vpp, f32p,
+                                                         ctypes.c_void_p, ctypes.c_int, i64p, i64p, ctypes.c_int32,
+                                                         ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                                         i64p, i64p, i64p, i64p]
         L.oracle_forward_bag.restype = ctypes.c_int
         L.oracle_forward_bag.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int32, i64p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int, f32p]
@@ -116,15 +130,25 @@ def double_to_half(x: float) -> int:
     return lib().oracle_double_to_half(float(x))
 
 
-def forward(tables: Sequence[np.ndarray], indices, offsets, B: int, pooling="sum") -> np.ndarray:
-    """Pooled activations [B, sum(D)] float32."""
+def bf16_to_double(bits: int) -> float:
+    return lib().oracle_bf16_to_double(int(bits))
+
+
+def double_to_bf16(x: float) -> int:
+    return lib().oracle_double_to_bf16(float(x))
+
+
+def forward(tables: Sequence[np.ndarray], indices, offsets, B: int, pooling="sum", out_dtype="f32") -> np.ndarray:
+    """Pooled activations [B, sum(D)]: float32, float16, or uint16 holding bfloat16 bit patterns (out_dtype
+    "f32" | "f16" | "bf16"); each value is rounded once from the fp64 sum."""
     dt, rows, D, ptrs = _tables(tables)
     indices, offsets = _i64(indices), _i64(offsets)
     assert offsets.shape[0] == len(tables) * B + 1 and offsets[-1] == indices.shape[0]
-    out = np.zeros((B, int(D.sum())), dtype=np.float32)
-    rc = lib().oracle_forward(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
-                              _p(indices, ctypes.c_int64), _p(offsets, ctypes.c_int64), B, _pooling(pooling),
-                              _p(out, ctypes.c_float))
+    np_dt = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[out_dtype]
+    out = np.zeros((B, int(D.sum())), dtype=np_dt)
+    rc = lib().oracle_forward_io(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
+                                 _p(indices, ctypes.c_int64), _p(offsets, ctypes.c_int64), B, _pooling(pooling),
+                                 out.ctypes.data, _IO[out_dtype])
     if rc:
         raise IndexError("id outside its table")
     return out
@@ -202,13 +226,15 @@ class BackwardResult:
 
 def backward_rowwise_adagrad(tables: List[np.ndarray], state: np.ndarray, grad_out: np.ndarray, indices, offsets,
                              B: int, pooling="sum", lr: float = 0.01, eps: float = 1e-8, c: float = 1.0,
-                             want_indices: bool = True) -> BackwardResult:
-    """In place on `tables` and `state`.  Returns the exact integer by-products of the sorted formulation."""
+                             want_indices: bool = True, grad_dtype: str = "f32") -> BackwardResult:
+    """In place on `tables` and `state`.  Returns the exact integer by-products of the sorted formulation.
+    grad_out is float32, float16, or uint16 holding bfloat16 bit patterns (grad_dtype "f32" | "f16" | "bf16")."""
     dt, rows, D, ptrs = _tables(tables)
     indices, offsets = _i64(indices), _i64(offsets)
     N = indices.shape[0]
     assert state.dtype == np.float32 and state.shape == (int(rows.sum()),) and state.flags["C_CONTIGUOUS"]
-    assert grad_out.dtype == np.float32 and grad_out.shape == (B, int(D.sum())) and grad_out.flags["C_CONTIGUOUS"]
+    want_np = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[grad_dtype]
+    assert grad_out.dtype == want_np and grad_out.shape == (B, int(D.sum())) and grad_out.flags["C_CONTIGUOUS"]
     assert offsets.shape[0] == len(tables) * B + 1 and offsets[-1] == N
     res = BackwardResult()
     n1 = max(N, 1)
@@ -221,11 +247,11 @@ def backward_rowwise_adagrad(tables: List[np.ndarray], state: np.ndarray, grad_o
     def ptr(a):
         return _p(a, ctypes.c_int64) if a is not None else null
 
-    U = lib().oracle_backward_rowwise_adagrad(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
-                                              _p(state, ctypes.c_float), _p(grad_out, ctypes.c_float),
-                                              _p(indices, ctypes.c_int64), _p(offsets, ctypes.c_int64), B,
-                                              _pooling(pooling), float(lr), float(eps), float(c),
-                                              ptr(ks), ptr(order), ptr(uniq), ptr(seg))
+    U = lib().oracle_backward_rowwise_adagrad_io(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
+                                                 _p(state, ctypes.c_float), grad_out.ctypes.data, _IO[grad_dtype],
+                                                 _p(indices, ctypes.c_int64), _p(offsets, ctypes.c_int64), B,
+                                                 _pooling(pooling), float(lr), float(eps), float(c),
+                                                 ptr(ks), ptr(order), ptr(uniq), ptr(seg))
     if U < 0:
         raise IndexError("id outside its table")
     res.U = int(U)

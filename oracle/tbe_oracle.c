@@ -73,6 +73,59 @@ uint16_t oracle_double_to_half(double x) {
     return (uint16_t)(sign | bits);
 }
 
+/* ---- bfloat16 (the upper 16 bits of a binary32) <-> double, round-to-nearest-even, by hand ------------ */
+double oracle_bf16_to_double(uint16_t b) {
+    int sign = (b >> 15) & 1;
+    int e = (b >> 7) & 0xFF;
+    int m = b & 0x7F;
+    double x;
+    if (e == 0) x = ldexp((double)m, -133);                 /* subnormal: m * 2^-7 * 2^-126 */
+    else if (e == 255) x = m ? NAN : INFINITY;
+    else x = ldexp((double)(128 + m), e - 134);             /* (1 + m/128) * 2^(e-127) */
+    return sign ? -x : x;
+}
+
+uint16_t oracle_double_to_bf16(double x) {
+    uint16_t sign = (uint16_t)(signbit(x) ? 0x8000u : 0u);
+    double a = fabs(x);
+    if (isnan(x)) return (uint16_t)(sign | 0x7FC0u);
+    if (isinf(x)) return (uint16_t)(sign | 0x7F80u);
+    if (a < ldexp(1.0, -134)) return sign;                  /* below half of the smallest subnormal (2^-133) */
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;
+    if (e < -126) e = -126;                                 /* subnormals share the spacing 2^-133 */
+    double ulp = ldexp(1.0, e - 7);
+    double v = nearbyint(a / ulp) * ulp;                    /* nearest even in the default rounding mode */
+    if (v >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
+    uint16_t bits;
+    if (v < ldexp(1.0, -126)) {
+        bits = (uint16_t)(v / ldexp(1.0, -133));
+    } else {
+        int ex2;
+        (void)frexp(v, &ex2);
+        int e2 = ex2 - 1;
+        double mant = v / ldexp(1.0, e2) - 1.0;
+        bits = (uint16_t)(((e2 + 127) << 7) | (int)(mant * 128.0));
+    }
+    return (uint16_t)(sign | bits);
+}
+
+/* element types of the pooled output / upstream gradient matrix */
+enum { ORACLE_IO_F32 = 0, ORACLE_IO_F16 = 1, ORACLE_IO_BF16 = 2 };
+
+static double load_io(const void* m, int io, int64_t e) {
+    if (io == ORACLE_IO_F32) return (double)((const float*)m)[e];
+    if (io == ORACLE_IO_F16) return oracle_half_to_double(((const uint16_t*)m)[e]);
+    return oracle_bf16_to_double(((const uint16_t*)m)[e]);
+}
+
+static void store_io(void* m, int io, int64_t e, double x) {   /* one rounding, from the fp64 value */
+    if (io == ORACLE_IO_F32) ((float*)m)[e] = (float)x;
+    else if (io == ORACLE_IO_F16) ((uint16_t*)m)[e] = oracle_double_to_half(x);
+    else ((uint16_t*)m)[e] = oracle_double_to_bf16(x);
+}
+
 static double load_w(const void* tab, int dtype, int64_t e) {
     if (dtype == ORACLE_F32) return (double)((const float*)tab)[e];
     return oracle_half_to_double(((const uint16_t*)tab)[e]);
@@ -92,8 +145,8 @@ static double bag_scale(const int64_t* offsets, int64_t bag, int pooling) {
 
 /* ---- forward -------------------------------------------------------------------------------- */
 /* One bag:  out_row[j] = s * sum_{p in bag} W_t[indices[p], j].  Returns -1 on an id outside [0, R_t). */
-int oracle_forward_bag(const void* table, int dtype, int64_t R, int32_t D, const int64_t* indices,
-                       int64_t start, int64_t end, int pooling, float* out_row) {
+int oracle_forward_bag_io(const void* table, int dtype, int64_t R, int32_t D, const int64_t* indices,
+                          int64_t start, int64_t end, int pooling, void* out, int out_io, int64_t out_elem) {
     double* acc = (double*)calloc((size_t)D, sizeof(double));
     for (int64_t p = start; p < end; ++p) {
         int64_t r = indices[p];
@@ -102,27 +155,37 @@ int oracle_forward_bag(const void* table, int dtype, int64_t R, int32_t D, const
     }
     int64_t L = end - start;
     double s = (pooling == ORACLE_SUM) ? 1.0 : (L > 0 ? 1.0 / (double)L : 0.0);
-    for (int32_t j = 0; j < D; ++j) out_row[j] = (float)(s * acc[j]);
+    for (int32_t j = 0; j < D; ++j) store_io(out, out_io, out_elem + j, s * acc[j]);
     free(acc);
     return 0;
 }
 
+int oracle_forward_bag(const void* table, int dtype, int64_t R, int32_t D, const int64_t* indices,
+                       int64_t start, int64_t end, int pooling, float* out_row) {
+    return oracle_forward_bag_io(table, dtype, R, D, indices, start, end, pooling, out_row, ORACLE_IO_F32, 0);
+}
+
 /* All bags: out is [B, sum(D)] row-major; bag (t,b) fills out[b, D_off[t] : D_off[t]+D_t]. */
-int oracle_forward(int32_t T, const int64_t* rows, const int32_t* D, int dtype, const void* const* tables,
-                   const int64_t* indices, const int64_t* offsets, int32_t B, int pooling, float* out) {
+int oracle_forward_io(int32_t T, const int64_t* rows, const int32_t* D, int dtype, const void* const* tables,
+                      const int64_t* indices, const int64_t* offsets, int32_t B, int pooling, void* out, int out_io) {
     int64_t sumD = 0;
     for (int32_t t = 0; t < T; ++t) sumD += D[t];
     int64_t doff = 0;
     for (int32_t t = 0; t < T; ++t) {
         for (int32_t b = 0; b < B; ++b) {
             int64_t bag = (int64_t)t * B + b;
-            int rc = oracle_forward_bag(tables[t], dtype, rows[t], D[t], indices, offsets[bag], offsets[bag + 1],
-                                        pooling, out + (int64_t)b * sumD + doff);
+            int rc = oracle_forward_bag_io(tables[t], dtype, rows[t], D[t], indices, offsets[bag], offsets[bag + 1],
+                                           pooling, out, out_io, (int64_t)b * sumD + doff);
             if (rc) return rc;
         }
         doff += D[t];
     }
     return 0;
+}
+
+int oracle_forward(int32_t T, const int64_t* rows, const int32_t* D, int dtype, const void* const* tables,
+                   const int64_t* indices, const int64_t* offsets, int32_t B, int pooling, float* out) {
+    return oracle_forward_io(T, rows, D, dtype, tables, indices, offsets, B, pooling, out, ORACLE_IO_F32);
 }
 
 /* ---- which rows appear: linearise, stable sort, run lengths ---------------------------------- */
@@ -217,12 +280,12 @@ int64_t oracle_row_gradient_by_scan(int32_t t, int64_t r, int32_t D, int64_t dof
  * segment in ascending position order (fp64), then one optimizer step.  Rows outside unique_rows are
  * never written.  Optional outputs (may be NULL): keys_sorted[N], order[N], unique_rows[N], seg_start[N+1].
  * Returns U (>= 0), or -1 on an invalid id. */
-int64_t oracle_backward_rowwise_adagrad(int32_t T, const int64_t* rows, const int32_t* D, int dtype,
-                                        void* const* tables /*in/out*/, float* state /*[sum rows] in/out*/,
-                                        const float* grad_out, const int64_t* indices, const int64_t* offsets,
-                                        int32_t B, int pooling, double lr, double eps, double c,
-                                        int64_t* keys_sorted_out, int64_t* order_out,
-                                        int64_t* unique_rows_out, int64_t* seg_start_out) {
+int64_t oracle_backward_rowwise_adagrad_io(int32_t T, const int64_t* rows, const int32_t* D, int dtype,
+                                           void* const* tables /*in/out*/, float* state /*[sum rows] in/out*/,
+                                           const void* grad_out, int grad_io, const int64_t* indices,
+                                           const int64_t* offsets, int32_t B, int pooling, double lr, double eps,
+                                           double c, int64_t* keys_sorted_out, int64_t* order_out,
+                                           int64_t* unique_rows_out, int64_t* seg_start_out) {
     int64_t N = offsets[(int64_t)T * B];
     int64_t sumD = 0;
     int32_t maxD = 0;
@@ -250,8 +313,7 @@ int64_t oracle_backward_rowwise_adagrad(int32_t T, const int64_t* rows, const in
                 int64_t bag = bag_of[order[i]];
                 int64_t b = bag - (int64_t)t * B;
                 double s = bag_scale(offsets, bag, pooling);
-                const float* go = grad_out + b * sumD + doff;
-                for (int32_t j = 0; j < Dt; ++j) g[j] += s * (double)go[j];
+                for (int32_t j = 0; j < Dt; ++j) g[j] += s * load_io(grad_out, grad_io, b * sumD + doff + j);
             }
             oracle_adagrad_row(tables[t], dtype, r, Dt, &state[uniq[u]], g, lr, eps, c);
         }
@@ -262,4 +324,14 @@ int64_t oracle_backward_rowwise_adagrad(int32_t T, const int64_t* rows, const in
     }
     free(keys); free(bag_of); free(ks); free(order); free(uniq); free(seg); free(g);
     return U;
+}
+
+int64_t oracle_backward_rowwise_adagrad(int32_t T, const int64_t* rows, const int32_t* D, int dtype,
+                                        void* const* tables, float* state, const float* grad_out,
+                                        const int64_t* indices, const int64_t* offsets, int32_t B, int pooling, double lr,
+                                        double eps, double c, int64_t* keys_sorted_out, int64_t* order_out,
+                                        int64_t* unique_rows_out, int64_t* seg_start_out) {
+    return oracle_backward_rowwise_adagrad_io(T, rows, D, dtype, tables, state, grad_out, ORACLE_IO_F32, indices, offsets,
+                                              B, pooling, lr, eps, c, keys_sorted_out, order_out, unique_rows_out,
+                                              seg_start_out);
 }

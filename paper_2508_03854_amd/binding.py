@@ -16,9 +16,14 @@ _LIB_PATH = os.environ.get("TBE355_LIB", os.path.join(_HERE, "libtbe355.so"))  #
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, EINDEX, EHIP = range(7)
 F32, F16 = 0, 1
 SUM, MEAN = 0, 1
+I64, I32 = 0, 1                       # tbe_index_dtype
+IO_F32, IO_F16, IO_BF16 = 0, 1, 2     # tbe_io_dtype
+_IDX = {torch.int64: I64, torch.int32: I32}
+_IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
+           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex",
            "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable", "tbe_timing_count", "tbe_timing_read",
            "tbe_calibration_copy", "tbe_status_string"]
 
@@ -56,6 +61,11 @@ def load_library():
     L.tbe_backward_rowwise_adagrad.restype = ctypes.c_int
     L.tbe_backward_rowwise_adagrad.argtypes = [vp, vp, vp, vp, i32, i64, ctypes.c_int, f32, f32, f32, vp, vp, vp,
                                                ctypes.c_size_t, vp]
+    L.tbe_forward_ex.restype = ctypes.c_int
+    L.tbe_forward_ex.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int, vp, ctypes.c_int, vp]
+    L.tbe_backward_rowwise_adagrad_ex.restype = ctypes.c_int
+    L.tbe_backward_rowwise_adagrad_ex.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int,
+                                                  f32, f32, f32, vp, vp, vp, ctypes.c_size_t, vp]
     L.tbe_debug_sorted.restype = ctypes.c_int
     L.tbe_debug_sorted.argtypes = [vp, vp, i32, i64] + [ctypes.POINTER(vp)] * 5
     L.tbe_poll_index_error.restype = ctypes.c_int
@@ -96,6 +106,12 @@ def _dev_ptr(t: Optional[torch.Tensor], dtype: torch.dtype, what: str) -> Option
     if not t.is_contiguous():
         raise ValueError(f"{what} must be contiguous")
     return t.data_ptr()
+
+
+def _index_dtype(indices: torch.Tensor, offsets: torch.Tensor) -> int:
+    if indices.dtype != offsets.dtype or indices.dtype not in _IDX:
+        raise TypeError(f"indices and offsets must both be int64 or both int32, got {indices.dtype} / {offsets.dtype}")
+    return _IDX[indices.dtype]
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
@@ -162,6 +178,50 @@ class TBE:
                                    _dev_ptr(out, torch.float32, "out"), _stream_ptr(stream))
         _check(st, "tbe_forward")
         return out
+
+    # ---- tbe_forward_ex
+    def forward_ex(self, tables: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,
+                   pooling: str = "sum", out: Optional[torch.Tensor] = None, out_dtype: torch.dtype = torch.float32,
+                   D_offsets: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """int64 or int32 indices/offsets (both the same); float32, float16 or bfloat16 out."""
+        if out is None:
+            out = torch.empty(B, self.sum_D, dtype=out_dtype, device=tables.device)
+        if out.dtype not in _IO:
+            raise TypeError(f"out must be float32, float16 or bfloat16, got {out.dtype}")
+        if tables.numel() != self.total_elems or out.shape != (B, self.sum_D):
+            raise ValueError("tables / out shape does not match the handle")
+        if offsets.numel() != self.T * B + 1:
+            raise ValueError("offsets must have T*B+1 entries")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_forward_ex(self._h, _dev_ptr(tables, self.torch_dtype, "tables"),
+                                      _dev_ptr(D_offsets, torch.int32, "D_offsets"),
+                                      _dev_ptr(indices, indices.dtype, "indices"),
+                                      _dev_ptr(offsets, offsets.dtype, "offsets"), idt, int(B), int(indices.numel()),
+                                      {"sum": SUM, "mean": MEAN}[pooling], _dev_ptr(out, out.dtype, "out"),
+                                      _IO[out.dtype], _stream_ptr(stream))
+        _check(st, "tbe_forward_ex")
+        return out
+
+    # ---- tbe_backward_rowwise_adagrad_ex
+    def backward_rowwise_adagrad_ex(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,
+                                    tables: torch.Tensor, state: torch.Tensor, workspace: torch.Tensor, *,
+                                    pooling: str = "sum", lr: float, eps: float, momentum_scale: float = 1.0,
+                                    stream: Optional[torch.cuda.Stream] = None) -> None:
+        """int64 or int32 indices/offsets (both the same); float32, float16 or bfloat16 grad_out."""
+        if tables.numel() != self.total_elems or state.numel() != self.total_rows:
+            raise ValueError("tables / state shape does not match the handle")
+        if grad_out.shape != (B, self.sum_D) or offsets.numel() != self.T * B + 1:
+            raise ValueError("grad_out / offsets shape does not match the handle")
+        if grad_out.dtype not in _IO:
+            raise TypeError(f"grad_out must be float32, float16 or bfloat16, got {grad_out.dtype}")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_backward_rowwise_adagrad_ex(
+            self._h, _dev_ptr(grad_out, grad_out.dtype, "grad_out"), _IO[grad_out.dtype],
+            _dev_ptr(indices, indices.dtype, "indices"), _dev_ptr(offsets, offsets.dtype, "offsets"), idt, int(B),
+            int(indices.numel()), {"sum": SUM, "mean": MEAN}[pooling], float(lr), float(eps), float(momentum_scale),
+            _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(state, torch.float32, "state"),
+            _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
+        _check(st, "tbe_backward_rowwise_adagrad_ex")
 
     # ---- tbe_backward_rowwise_adagrad
     def backward_rowwise_adagrad(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,

@@ -10,7 +10,7 @@ namespace tbe {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Workspace carve(const tbe_handle* h, int64_t N, int32_t B) {
+Workspace carve(const tbe_handle* h, int64_t N) {
     Workspace w;
     memset(&w, 0, sizeof(w));
     const size_t n = (size_t)(N > 0 ? N : 1);
@@ -49,12 +49,6 @@ Workspace carve(const tbe_handle* h, int64_t N, int32_t B) {
     w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);
-#ifdef TBE_GRAD_TABLE_MAJOR
-    w.grad_tm_bytes = 4 * (size_t)B * (size_t)h->sumD;
-    w.grad_tm = take(w.grad_tm_bytes);
-#else
-    (void)B;
-#endif
     w.total = off;
     return w;
 }
@@ -193,45 +187,61 @@ tbe_status tbe_workspace_bytes(const tbe_handle* h, int32_t B, int64_t max_nnz, 
     if (!h || !bytes) return TBE_EINVAL;
     const tbe_status st = check_batch(h, B, max_nnz);
     if (st != TBE_OK) return st;
-    *bytes = carve(h, max_nnz, B).total;
+    *bytes = carve(h, max_nnz).total;
     return TBE_OK;
 }
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const int64_t* indices,
-                       const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
-                       void* hip_stream) {
+static bool io_ok(int io) { return io == TBE_IO_F32 || io == TBE_IO_F16 || io == TBE_IO_BF16; }
+static bool idx_ok(int d) { return d == TBE_I64 || d == TBE_I32; }
+
+tbe_status tbe_forward_ex(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const void* indices,
+                          const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
+                          void* out, tbe_io_dtype out_dtype, void* hip_stream) {
     if (!h || !tables || !offsets || !out || (!indices && nnz > 0)) return TBE_EINVAL;
     if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
+    if (!io_ok(out_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
     const tbe_status st = check_batch(h, B, nnz);
     if (st != TBE_OK) return st;
-    if (!aligned(tables, 16) || !aligned(out, 16) || !aligned(indices, 8) || !aligned(offsets, 8)) return TBE_EINVAL;
-    const hipError_t e = launch_forward(h, tables, D_offsets ? D_offsets : h->d_D_off, indices, offsets, B, nnz, pooling,
-                                        out, static_cast<hipStream_t>(hip_stream));
+    const size_t ia = index_dtype == TBE_I32 ? 4 : 8;
+    if (!aligned(tables, 16) || !aligned(out, 16) || !aligned(indices, ia) || !aligned(offsets, ia)) return TBE_EINVAL;
+    const hipError_t e = launch_forward(h, tables, D_offsets ? D_offsets : h->d_D_off, indices, offsets,
+                                        index_dtype == TBE_I32, B, nnz, pooling, out, (int)out_dtype,
+                                        static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
-tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
-                                        const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
-                                        float eps, float momentum_scale, void* tables, float* state, void* workspace,
-                                        size_t workspace_bytes, void* hip_stream) {
+tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const int64_t* indices,
+                       const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
+                       void* hip_stream) {
+    return tbe_forward_ex(h, tables, D_offsets, indices, offsets, TBE_I64, B, nnz, pooling, out, TBE_IO_F32, hip_stream);
+}
+
+tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                           const void* indices, const void* offsets, tbe_index_dtype index_dtype,
+                                           int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
+                                           float momentum_scale, void* tables, float* state, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
     if (!h || !grad_out || !offsets || !tables || !state || (!indices && nnz > 0)) return TBE_EINVAL;
     if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
+    if (!io_ok(grad_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
     if (!isfinite(lr) || !isfinite(eps) || eps < 0.f || !isfinite(momentum_scale) || !(momentum_scale > 0.f))
         return TBE_EINVAL;
     const tbe_status st = check_batch(h, B, nnz);
     if (st != TBE_OK) return st;
-    if (!aligned(tables, 16) || !aligned(grad_out, 16) || !aligned(state, 4) || !aligned(indices, 8) ||
-        !aligned(offsets, 8))
+    const size_t ia = index_dtype == TBE_I32 ? 4 : 8;
+    if (!aligned(tables, 16) || !aligned(grad_out, 16) || !aligned(state, 4) || !aligned(indices, ia) ||
+        !aligned(offsets, ia))
         return TBE_EINVAL;
     if (nnz == 0) return TBE_OK;  // no id appears in the batch: no row has a gradient
     if (!workspace || !aligned(workspace, 256)) return TBE_EINVAL;
-    const Workspace w = carve(h, nnz, B);
+    const Workspace w = carve(h, nnz);
     if (workspace_bytes < w.total) return TBE_EWORKSPACE;
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = launch_linearize(h, indices, offsets, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
+    const int idx32 = index_dtype == TBE_I32;
+    hipError_t e = launch_linearize(h, indices, offsets, idx32, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
                                     reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
     if (e != hipSuccess) return TBE_EHIP;
     int buf = 0;
@@ -239,8 +249,17 @@ tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_o
     if (e != hipSuccess) return TBE_EHIP;
     e = launch_run_lengths(h, w, ws, buf, nnz, s);
     if (e != hipSuccess) return TBE_EHIP;
-    e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, offsets, B, pooling, lr, eps, momentum_scale, tables, state, s);
+    e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, (int)grad_dtype, offsets, idx32, B, pooling, lr, eps,
+                              momentum_scale, tables, state, s);
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
+                                        const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
+                                        float eps, float momentum_scale, void* tables, float* state, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+    return tbe_backward_rowwise_adagrad_ex(h, grad_out, TBE_IO_F32, indices, offsets, TBE_I64, B, nnz, pooling, lr, eps,
+                                           momentum_scale, tables, state, workspace, workspace_bytes, hip_stream);
 }
 
 tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int64_t nnz, const uint32_t** keys_sorted,
@@ -249,7 +268,7 @@ tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int
     if (!h || !workspace) return TBE_EINVAL;
     const tbe_status st = check_batch(h, B, nnz);
     if (st != TBE_OK) return st;
-    const Workspace w = carve(h, nnz, B);
+    const Workspace w = carve(h, nnz);
     const int passes = (h->key_bits + 7) / 8;
     const int buf = passes & 1;  // every pass flips the double buffer, starting from 0
     char* ws = static_cast<char*>(workspace);

@@ -61,9 +61,8 @@ struct SegArgs {
     const uint32_t* seg_start;
     const uint32_t* counters;     // [0]=U, [1]=n_long, [2]=n_chunks
     const uint32_t* bag_sorted;   // linear bag id of every sorted position
-    const int64_t* offsets;
-    const float* grad_out;
-    const float* grad_tm;         // table-major copy of grad_out, or nullptr
+    IdxView offsets;
+    const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT
     const int32_t* D_off;
     const int64_t* row_base;
     const int64_t* w_off;
@@ -82,27 +81,8 @@ struct SegArgs {
     uint32_t cap_long, cap_chunks;
 };
 
-// Where the upstream gradient of table t lives: either in the caller's [B, sum(D)] matrix (column block
-// D_off[t], row stride sum(D)), or in the table-major copy made by grad_to_table_major (block t is a
-// contiguous [B, D_t] matrix, so the slices of consecutive bags are adjacent in memory).
-struct GradView {
-    const float* base;
-    int64_t stride;
-};
-__device__ __forceinline__ GradView grad_view(const SegArgs& a, int t, int d0, int D) {
-    GradView v;
-    if (a.grad_tm) {
-        v.base = a.grad_tm + (int64_t)a.B * d0;
-        v.stride = D;
-    } else {
-        v.base = a.grad_out + d0;
-        v.stride = a.sumD;
-    }
-    return v;
-}
-
 template <bool MEAN>
-__device__ __forceinline__ float bag_scale(const int64_t* __restrict__ offsets, uint32_t bag) {
+__device__ __forceinline__ float bag_scale(const IdxView offsets, uint32_t bag) {
     if (!MEAN) return 1.f;
     const int64_t L = offsets[(int64_t)bag + 1] - offsets[bag];
     return L > 0 ? 1.f / (float)L : 0.f;
@@ -111,11 +91,11 @@ __device__ __forceinline__ float bag_scale(const int64_t* __restrict__ offsets, 
 // Whole-wavefront reduction of sorted positions [s, e) of ONE row:
 // acc += sum of scale(bag) * grad_out[b, d0 + col .. col+3]; the groups take interleaved positions and
 // fold_groups() completes the sum.  NC = 256-column chunks per row.
-template <int NC, bool MEAN>
-__device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeom& g, const float* __restrict__ gcol,
+template <int NC, bool MEAN, typename GT>
+__device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeom& g, const GT* __restrict__ gcol,
                                                const int64_t sumD, const int64_t bag0,
-                                               const uint32_t* __restrict__ bag_sorted,
-                                               const int64_t* __restrict__ offsets, const uint32_t s, const uint32_t e) {
+                                               const uint32_t* __restrict__ bag_sorted, const IdxView offsets,
+                                               const uint32_t s, const uint32_t e) {
     const int lane = lane_id();
     for (uint32_t base = s; base < e; base += kWave) {
         const int n = (int)((e - base) < (uint32_t)kWave ? (e - base) : (uint32_t)kWave);
@@ -127,7 +107,7 @@ __device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeo
             my_s = bag_scale<MEAN>(offsets, bag);
         }
         for (int k0 = 0; k0 < n; k0 += kSegUnroll * g.G) {
-            float4 x[kSegUnroll][NC];
+            typename GradIO<GT>::raw_t x[kSegUnroll][NC];
             float sc[kSegUnroll];
 #pragma unroll
             for (int u = 0; u < kSegUnroll; ++u) {
@@ -138,24 +118,24 @@ __device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeo
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const int col = g.lc + c * kWave * 4;
-                    x[u][c] = (on && col < g.D) ? *reinterpret_cast<const float4*>(gcol + (int64_t)b * sumD + col)
-                                                : make_float4(0.f, 0.f, 0.f, 0.f);
+                    x[u][c] = (on && col < g.D) ? GradIO<GT>::load(gcol + (int64_t)b * sumD + col) : GradIO<GT>::zero();
                 }
             }
 #pragma unroll
             for (int u = 0; u < kSegUnroll; ++u)
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
+                    const float4 f = GradIO<GT>::to_float(x[u][c]);
                     if (MEAN) {
-                        acc[c][0] = fmaf(sc[u], x[u][c].x, acc[c][0]);
-                        acc[c][1] = fmaf(sc[u], x[u][c].y, acc[c][1]);
-                        acc[c][2] = fmaf(sc[u], x[u][c].z, acc[c][2]);
-                        acc[c][3] = fmaf(sc[u], x[u][c].w, acc[c][3]);
+                        acc[c][0] = fmaf(sc[u], f.x, acc[c][0]);
+                        acc[c][1] = fmaf(sc[u], f.y, acc[c][1]);
+                        acc[c][2] = fmaf(sc[u], f.z, acc[c][2]);
+                        acc[c][3] = fmaf(sc[u], f.w, acc[c][3]);
                     } else {
-                        acc[c][0] += x[u][c].x;
-                        acc[c][1] += x[u][c].y;
-                        acc[c][2] += x[u][c].z;
-                        acc[c][3] += x[u][c].w;
+                        acc[c][0] += f.x;
+                        acc[c][1] += f.y;
+                        acc[c][2] += f.z;
+                        acc[c][3] += f.w;
                     }
                 }
         }
@@ -206,29 +186,6 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
             }
         }
         if (g.lc == 0) *vptr = v_new;
-    }
-}
-
-// ---- table-major copy of the upstream gradient ---------------------------------------------------------
-// grad_tm[B * D_off[t] + b * D_t + j] = grad_out[b * sum(D) + D_off[t] + j].  One workgroup row per sample,
-// float4 per thread, both sides coalesced.
-__global__ __launch_bounds__(256) void grad_to_table_major_kernel(const float* __restrict__ grad_out,
-                                                                  float* __restrict__ grad_tm,
-                                                                  const int32_t* __restrict__ D_off, const int T,
-                                                                  const int B, const int sumD) {
-    const int b = blockIdx.x;
-    const float* src = grad_out + (int64_t)b * sumD;
-    for (int col = threadIdx.x * 4; col < sumD; col += blockDim.x * 4) {
-        int lo = 0, hi = T;  // table of this column: last t with D_off[t] <= col
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (D_off[mid + 1] > col) hi = mid;
-            else lo = mid + 1;
-        }
-        const int d0 = D_off[lo];
-        const int D = D_off[lo + 1] - d0;
-        *reinterpret_cast<float4*>(grad_tm + (int64_t)B * d0 + (int64_t)b * D + (col - d0)) =
-            *reinterpret_cast<const float4*>(src + col);
     }
 }
 
@@ -418,7 +375,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_bounds_kernel(const SegA
 // is accumulated over the sweeps by the same workgroup; the kernel boundary orders those updates.
 // (Handing out units in strict list order through an atomic ticket was tried: device-scope atomics on one
 // address cost more than the better alignment gained.)
-template <int NC, bool MEAN>
+template <int NC, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial_kernel(const SegArgs a, const uint32_t sweep) {
     __shared__ float s_part[kSegThreads / kWave][NC * 256];
     const uint32_t nunits = a.counters[3];
@@ -466,8 +423,8 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
             float acc[NC][4];
 #pragma unroll
             for (int cc = 0; cc < NC; ++cc) acc[cc][0] = acc[cc][1] = acc[cc][2] = acc[cc][3] = 0.f;
-            const GradView gv = grad_view(a, t, d0, g.D);
-            segment_reduce<NC, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t * a.B, a.bag_sorted, a.offsets, ws_, we_);
+            segment_reduce<NC, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + d0, a.sumD, (int64_t)t * a.B,
+                                         a.bag_sorted, a.offsets, ws_, we_);
             fold_groups<NC>(acc, g);
             if (g.sub == 0) {
 #pragma unroll
@@ -494,7 +451,7 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
 }
 
 // ---- 3a. rows with at most kSegChunk lookups, all tables at most 256 columns wide ------------------
-template <typename WT, bool MEAN>
+template <typename WT, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
@@ -539,8 +496,8 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                 const int t_r = __shfl(t, r, kWave);
                 const float v_r = __shfl(v, r, kWave);
                 float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
-                const GradView gv = grad_view(a, t_r, a.D_off[t_r], g.D);
-                segment_reduce<1, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t_r * a.B, a.bag_sorted,
+                segment_reduce<1, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + a.D_off[t_r], a.sumD,
+                                            (int64_t)t_r * a.B, a.bag_sorted,
                                         a.offsets, s_r, s_r + len_r);
                 fold_groups<1>(acc, g);
                 WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
@@ -571,8 +528,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             const float gv = __shfl(v, gi, kWave);
             const int goff = (int)(gs - s_r);
             const bool col_on = g.lc < g.D;
-            const GradView gvw = grad_view(a, gt, a.D_off[gt], g.D);
-            const float* gcol = gvw.base + g.lc;
+            const GT* gcol = static_cast<const GT*>(a.grad_out) + a.D_off[gt] + g.lc;
             const int64_t bag0 = (int64_t)gt * a.B;
             WT* wrow = tables + a.w_off[gt] + ((int64_t)gkey - a.row_base[gt]) * g.D;
             uint32_t lmax = glen;  // longest row of the round (wave-uniform loop bound)
@@ -582,7 +538,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             }
             float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
             for (uint32_t q0 = 0; q0 < lmax; q0 += kSegUnroll) {
-                float4 x[kSegUnroll];
+                typename GradIO<GT>::raw_t x[kSegUnroll];
                 float sc[kSegUnroll];
 #pragma unroll
                 for (int uu = 0; uu < kSegUnroll; ++uu) {
@@ -591,21 +547,21 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                     const uint32_t bag = __shfl(my_bag, src, kWave);
                     sc[uu] = MEAN ? __shfl(my_s, src, kWave) : 1.f;
                     const bool on = qi < glen && col_on;
-                    x[uu] = on ? *reinterpret_cast<const float4*>(gcol + ((int64_t)bag - bag0) * gvw.stride)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
+                    x[uu] = on ? GradIO<GT>::load(gcol + ((int64_t)bag - bag0) * a.sumD) : GradIO<GT>::zero();
                 }
 #pragma unroll
                 for (int uu = 0; uu < kSegUnroll; ++uu) {
+                    const float4 f = GradIO<GT>::to_float(x[uu]);
                     if (MEAN) {
-                        acc[0][0] = fmaf(sc[uu], x[uu].x, acc[0][0]);
-                        acc[0][1] = fmaf(sc[uu], x[uu].y, acc[0][1]);
-                        acc[0][2] = fmaf(sc[uu], x[uu].z, acc[0][2]);
-                        acc[0][3] = fmaf(sc[uu], x[uu].w, acc[0][3]);
+                        acc[0][0] = fmaf(sc[uu], f.x, acc[0][0]);
+                        acc[0][1] = fmaf(sc[uu], f.y, acc[0][1]);
+                        acc[0][2] = fmaf(sc[uu], f.z, acc[0][2]);
+                        acc[0][3] = fmaf(sc[uu], f.w, acc[0][3]);
                     } else {
-                        acc[0][0] += x[uu].x;
-                        acc[0][1] += x[uu].y;
-                        acc[0][2] += x[uu].z;
-                        acc[0][3] += x[uu].w;
+                        acc[0][0] += f.x;
+                        acc[0][1] += f.y;
+                        acc[0][2] += f.z;
+                        acc[0][3] += f.w;
                     }
                 }
             }
@@ -616,7 +572,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
 }
 
 // ---- 3b. same rows, any width up to 1024 columns: one wavefront per row ----------------------------
-template <typename WT, bool MEAN>
+template <typename WT, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     const uint32_t U = a.counters[0];
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
@@ -637,8 +593,8 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         float acc[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-        const GradView gv = grad_view(a, t, d0, g.D);
-        segment_reduce<4, MEAN>(acc, g, gv.base, gv.stride, (int64_t)t * a.B, a.bag_sorted, a.offsets, s, e);
+        segment_reduce<4, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + d0, a.sumD, (int64_t)t * a.B, a.bag_sorted,
+                                    a.offsets, s, e);
         fold_groups<4>(acc, g);
         adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], g.sub == 0, a.lr, a.eps, a.inv_c);
     }
@@ -705,25 +661,52 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
     }
 }
 
-hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const float* grad_out,
-                                 const int64_t* offsets, int32_t B, tbe_pooling pooling, float lr, float eps, float c,
-                                 void* tables, float* state, hipStream_t s) {
+// the two row-update kernels and the hot-row reduction for one gradient element type
+template <typename GT>
+static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* counters, bool mean, bool narrow,
+                               hipStream_t s) {
+    const bool f32 = h->dtype == TBE_F32;
+    if (narrow) {
+        if (f32) {
+            if (mean) seg_update_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            else seg_update_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+        } else {
+            if (mean) seg_update_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            else seg_update_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+        }
+    } else {
+        if (f32) {
+            if (mean) seg_update_wide_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            else seg_update_wide_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+        } else {
+            if (mean) seg_update_wide_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            else seg_update_wide_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+        }
+    }
+}
+
+template <typename GT>
+static void launch_long_partial(const SegArgs& a, uint32_t sweep, bool mean, bool narrow, hipStream_t s) {
+    if (narrow) {
+        if (mean) seg_long_partial_kernel<1, true, GT><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sweep);
+        else seg_long_partial_kernel<1, false, GT><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sweep);
+    } else {
+        if (mean) seg_long_partial_kernel<4, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
+        else seg_long_partial_kernel<4, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
+    }
+}
+
+hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,
+                                 int grad_io, const void* offsets, int idx32, int32_t B, tbe_pooling pooling, float lr,
+                                 float eps, float c, void* tables, float* state, hipStream_t s) {
     SegArgs a;
     a.keys_unique = reinterpret_cast<const uint32_t*>(ws + w.vals[spare]);
     a.seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     a.counters = counters;
     a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[spare]);
-    a.offsets = offsets;
+    a.offsets = IdxView{offsets, idx32};
     a.grad_out = grad_out;
-    a.grad_tm = nullptr;
-    if (w.grad_tm_bytes) {
-        float* gtm = reinterpret_cast<float*>(ws + w.grad_tm);
-        LaunchTimer tm(h, s, "grad_to_table_major");
-        grad_to_table_major_kernel<<<B, 256, 0, s>>>(grad_out, gtm, h->d_D_off, h->T, B, h->sumD);
-        tm.done();
-        a.grad_tm = gtm;
-    }
     a.D_off = h->d_D_off;
     a.row_base = h->d_row_base;
     a.w_off = h->d_w_off;
@@ -754,23 +737,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.raw_long = reinterpret_cast<uint2*>(ws + w.raw_long);
     {   // rows with at most kSegChunk lookups; the others are noted for the long-row path
         LaunchTimer tm(h, s, "seg_update");
-        if (narrow) {
-            if (f32) {
-                if (mean) seg_update_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            } else {
-                if (mean) seg_update_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            }
-        } else {
-            if (f32) {
-                if (mean) seg_update_wide_kernel<float, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_wide_kernel<float, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            } else {
-                if (mean) seg_update_wide_kernel<__half, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_wide_kernel<__half, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            }
-        }
+        if (grad_io == 0) launch_row_updates<float>(h, a, counters, mean, narrow, s);
+        else if (grad_io == 1) launch_row_updates<__half>(h, a, counters, mean, narrow, s);
+        else launch_row_updates<bf16_t>(h, a, counters, mean, narrow, s);
         tm.done();
     }
     {
@@ -787,13 +756,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         uint32_t nsweeps = slices_for((uint32_t)B, (uint32_t)h->maxD) / 8u;
         if (nsweeps < 1u) nsweeps = 1u;
         for (uint32_t sw = 0; sw < nsweeps; ++sw) {
-            if (narrow) {
-                if (mean) seg_long_partial_kernel<1, true><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sw);
-                else seg_long_partial_kernel<1, false><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sw);
-            } else {
-                if (mean) seg_long_partial_kernel<4, true><<<kSegBlocks, kSegThreads, 0, s>>>(a, sw);
-                else seg_long_partial_kernel<4, false><<<kSegBlocks, kSegThreads, 0, s>>>(a, sw);
-            }
+            if (grad_io == 0) launch_long_partial<float>(a, sw, mean, narrow, s);
+            else if (grad_io == 1) launch_long_partial<__half>(a, sw, mean, narrow, s);
+            else launch_long_partial<bf16_t>(a, sw, mean, narrow, s);
         }
         tm.done();
     }

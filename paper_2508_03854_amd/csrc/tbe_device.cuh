@@ -53,6 +53,77 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* smem, 
     return wbase + inc - v;
 }
 
+// ---- ids and offsets: int64 or int32 at the boundary --------------------------------------------------
+struct IdxView {
+    const void* p;
+    int is32;
+    __device__ __forceinline__ int64_t operator[](int64_t i) const {
+        return is32 ? (int64_t)static_cast<const int32_t*>(p)[i] : static_cast<const int64_t*>(p)[i];
+    }
+};
+
+// ---- pooled output / upstream gradient element types: float, IEEE binary16, bfloat16 ---------------------
+struct bf16_t { unsigned short bits; };  // bfloat16 = the upper half of a binary32
+
+__device__ __forceinline__ float bf16_to_float(unsigned short b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ unsigned short float_to_bf16_rn(float x) {  // round to nearest even; NaN stays NaN
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (unsigned short)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+// Four consecutive elements of the upstream gradient.  A fragment stays in its raw form between the load
+// and its use, so that several loads can be in flight before the first conversion needs its data.
+template <typename GT>
+struct GradIO;
+template <>
+struct GradIO<float> {
+    using raw_t = float4;
+    static __device__ __forceinline__ raw_t load(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ __forceinline__ raw_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ float4 to_float(const raw_t& r) { return r; }
+};
+template <>
+struct GradIO<__half> {
+    using raw_t = uint2;
+    static __device__ __forceinline__ raw_t load(const __half* p) { return *reinterpret_cast<const uint2*>(p); }
+    static __device__ __forceinline__ raw_t zero() { return make_uint2(0u, 0u); }
+    static __device__ __forceinline__ float4 to_float(const raw_t& r) {
+        return make_float4(__half2float(__ushort_as_half((unsigned short)(r.x & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(r.x >> 16))),
+                           __half2float(__ushort_as_half((unsigned short)(r.y & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(r.y >> 16))));
+    }
+};
+template <>
+struct GradIO<bf16_t> {
+    using raw_t = uint2;
+    static __device__ __forceinline__ raw_t load(const bf16_t* p) { return *reinterpret_cast<const uint2*>(p); }
+    static __device__ __forceinline__ raw_t zero() { return make_uint2(0u, 0u); }
+    static __device__ __forceinline__ float4 to_float(const raw_t& r) {
+        return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                           __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+    }
+};
+
+// store four consecutive elements; io = 0 float, 1 binary16, 2 bfloat16 (one rounding to nearest even)
+__device__ __forceinline__ void store4_from_float(void* base, int io, int64_t elem, float a, float b, float c, float d) {
+    if (io == 0) {
+        *reinterpret_cast<float4*>(static_cast<float*>(base) + elem) = make_float4(a, b, c, d);
+    } else {
+        unsigned short h0, h1, h2, h3;
+        if (io == 1) {
+            h0 = __half_as_ushort(__float2half_rn(a)); h1 = __half_as_ushort(__float2half_rn(b));
+            h2 = __half_as_ushort(__float2half_rn(c)); h3 = __half_as_ushort(__float2half_rn(d));
+        } else {
+            h0 = float_to_bf16_rn(a); h1 = float_to_bf16_rn(b); h2 = float_to_bf16_rn(c); h3 = float_to_bf16_rn(d);
+        }
+        *reinterpret_cast<uint2*>(static_cast<unsigned short*>(base) + elem) =
+            make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+    }
+}
+
 // ---- 16-byte row fragments ---------------------------------------------------------------------
 // RowIO<WT>::kVec elements of a table row travel in one 16-byte load.
 template <typename WT>

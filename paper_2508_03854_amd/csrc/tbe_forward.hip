@@ -22,8 +22,9 @@ constexpr int kFwdThreads = 256;
 // NC = number of 64-lane column chunks a row needs (1 when D <= 64 * kVec); U = rows in flight per group.
 template <typename WT, int NC, int U, bool MEAN>
 __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const int D, const int64_t R,
-                                            const int64_t* __restrict__ indices, const int64_t start,
-                                            const int64_t end, float* __restrict__ out_row, int32_t* err) {
+                                            const IdxView indices, const int64_t start, const int64_t end,
+                                            void* __restrict__ out, const int out_io, const int64_t out_elem,
+                                            int32_t* err) {
     constexpr int V = RowIO<WT>::kVec;
     using raw_t = typename RowIO<WT>::raw_t;
     const int lane = lane_id();
@@ -86,9 +87,8 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
             if (col < D) {
 #pragma unroll
                 for (int v4 = 0; v4 < V; v4 += 4) {
-                    *reinterpret_cast<float4*>(out_row + col + v4) =
-                        make_float4(acc[c][v4] * scale, acc[c][v4 + 1] * scale, acc[c][v4 + 2] * scale,
-                                    acc[c][v4 + 3] * scale);
+                    store4_from_float(out, out_io, out_elem + col + v4, acc[c][v4] * scale, acc[c][v4 + 1] * scale,
+                                      acc[c][v4 + 2] * scale, acc[c][v4 + 3] * scale);
                 }
             }
         }
@@ -99,10 +99,10 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
 // 8 wavefronts per SIMD; the host picks the kernel from the widest table of the handle.
 template <typename WT, int NC, int U, bool MEAN>
 __global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forward_kernel(
-    const WT* __restrict__ weights, const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
     const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
-    const int32_t B, const int64_t nbags, const int64_t nnz, const int32_t sumD, float* __restrict__ out,
-    int32_t* err) {
+    const int32_t B, const int64_t nbags, const int64_t nnz, const int32_t sumD, void* __restrict__ out,
+    const int out_io, int32_t* err) {
     const int64_t bag = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
     if (bag >= nbags) return;
     const int32_t t = (int32_t)(bag / B);
@@ -115,24 +115,26 @@ __global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forw
     int64_t end = offsets[bag + 1];
     start = start < 0 ? 0 : (start > nnz ? nnz : start);
     end = end < start ? start : (end > nnz ? nnz : end);
-    forward_bag<WT, NC, U, MEAN>(weights + w_off[t], D, R, indices, start, end, out + (int64_t)b * sumD + d0, err);
+    forward_bag<WT, NC, U, MEAN>(weights + w_off[t], D, R, indices, start, end, out, out_io, (int64_t)b * sumD + d0, err);
 }
 
 template <typename WT, int NC, int U>
-static void launch_forward_nc(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
-                              const int64_t* offsets, int32_t B, int64_t nbags, int64_t nnz, bool mean, float* out,
-                              dim3 grid, hipStream_t s) {
+static void launch_forward_nc(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const IdxView indices,
+                              const IdxView offsets, int32_t B, int64_t nbags, int64_t nnz, bool mean, void* out,
+                              int out_io, dim3 grid, hipStream_t s) {
     const WT* w = static_cast<const WT*>(tables);
     if (mean)
         forward_kernel<WT, NC, U, true><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
-                                                                     h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
+                                                                     h->d_row_base, B, nbags, nnz, h->sumD, out, out_io, h->d_err);
     else
         forward_kernel<WT, NC, U, false><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
-                                                                      h->d_row_base, B, nbags, nnz, h->sumD, out, h->d_err);
+                                                                      h->d_row_base, B, nbags, nnz, h->sumD, out, out_io, h->d_err);
 }
 
-hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
-                          const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out, hipStream_t s) {
+hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const void* indices_p,
+                          const void* offsets_p, int idx32, int32_t B, int64_t nnz, tbe_pooling pooling, void* out,
+                          int out_io, hipStream_t s) {
+    const IdxView indices{indices_p, idx32}, offsets{offsets_p, idx32};
     const int64_t nbags = (int64_t)h->T * B;
     if (nbags == 0) return hipSuccess;
     const int wpb = kFwdThreads / kWave;
@@ -140,12 +142,12 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     LaunchTimer tm(h, s, "forward_pool");
     const bool mean = pooling == TBE_MEAN;
     if (h->dtype == TBE_F32) {
-        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
-        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
-        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
+        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
+        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
+        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
     } else {
-        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
-        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, grid, s);
+        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
+        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
     }
     tm.done();
     return hipGetLastError();

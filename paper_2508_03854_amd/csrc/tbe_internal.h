@@ -59,13 +59,13 @@ struct Workspace {
     // keys/vals: radix double buffers of N+1 words each.  After the sort the buffer pair that does not hold the
     // result is reused: keys[spare] <- bag id of every sorted position, vals[spare] <- unique_rows.
     size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, raw_long, long_list,
-        unit_list, bounds, partial, grad_tm, grad_tm_bytes, total;
+        unit_list, bounds, partial, total;
     int radix_blocks;     // G
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;
     int64_t cap_long, cap_chunks, cap_units;
 };
-Workspace carve(const tbe_handle* h, int64_t N, int32_t B);
+Workspace carve(const tbe_handle* h, int64_t N);
 
 // RAII-free helper: brackets one kernel launch with events when timing is on.
 struct LaunchTimer {
@@ -76,19 +76,20 @@ struct LaunchTimer {
     void done();
 };
 
-// launchers (each returns hipGetLastError() after its launches)
-hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const int64_t* indices,
-                          const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
-                          hipStream_t s);
-hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
+// launchers (each returns hipGetLastError() after its launches).  idx32: ids and offsets are int32 instead of
+// int64; out_io / grad_io: 0 float, 1 binary16, 2 bfloat16.
+hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const void* indices,
+                          const void* offsets, int idx32, int32_t B, int64_t nnz, tbe_pooling pooling, void* out,
+                          int out_io, hipStream_t s);
+hipError_t launch_linearize(const tbe_handle* h, const void* indices, const void* offsets, int idx32, int32_t B, int64_t N,
                             uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s);
 // sorts keys[0] of the workspace with the positions 0..N-1 as payload; returns in *result_buf which buffer pair
 // (0/1) holds the sorted keys and positions
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
 // `sorted` is the buffer index (0/1) that holds the sorted (key, position) pairs; the other pair is overwritten
 hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);
-hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const float* grad_out,
-                                 const int64_t* offsets, int32_t B, tbe_pooling pooling, float lr, float eps, float c,
-                                 void* tables, float* state, hipStream_t s);
+hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,
+                                 int grad_io, const void* offsets, int idx32, int32_t B, tbe_pooling pooling, float lr,
+                                 float eps, float c, void* tables, float* state, hipStream_t s);
 
 }  // namespace tbe

@@ -12,7 +12,7 @@ namespace tbe {
 constexpr int kLinThreads = 256;
 
 // first i in [lo, hi] with a[i] > x   (caller guarantees a[hi] > x)
-__device__ __forceinline__ int64_t upper_bound_i64(const int64_t* __restrict__ a, int64_t lo, int64_t hi, int64_t x) {
+__device__ __forceinline__ int64_t upper_bound_i64(const IdxView a, int64_t lo, int64_t hi, int64_t x) {
     while (lo < hi) {
         const int64_t mid = lo + ((hi - lo) >> 1);
         if (a[mid] > x) hi = mid;
@@ -24,8 +24,7 @@ __device__ __forceinline__ int64_t upper_bound_i64(const int64_t* __restrict__ a
 // A block owns kLinTile consecutive positions.  It finds the bags that own its first and last position
 // with two binary searches in the global offsets, stages that offsets segment in LDS (relative to the
 // tile start), and every thread then finds the bag of its position with a short search in LDS.
-__global__ __launch_bounds__(kLinThreads) void linearize_kernel(const int64_t* __restrict__ indices,
-                                                                const int64_t* __restrict__ offsets,
+__global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView indices, const IdxView offsets,
                                                                 const int64_t nbags, const int32_t B,
                                                                 const int64_t* __restrict__ row_base,
                                                                 const uint32_t invalid_key, const int64_t N,
@@ -89,8 +88,9 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const int64_t* _
     }
 }
 
-hipError_t launch_linearize(const tbe_handle* h, const int64_t* indices, const int64_t* offsets, int32_t B, int64_t N,
-                            uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s) {
+hipError_t launch_linearize(const tbe_handle* h, const void* indices_p, const void* offsets_p, int idx32, int32_t B,
+                            int64_t N, uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s) {
+    const IdxView indices{indices_p, idx32}, offsets{offsets_p, idx32};
     const int64_t nbags = (int64_t)h->T * B;
     const unsigned grid = (unsigned)((N + kLinTile - 1) / kLinTile);
     LaunchTimer tm(h, s, "linearize");

@@ -54,32 +54,79 @@ def half_ulp_distance(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return np.abs(ordered(a) - ordered(b))
 
 
+_IO_TORCH = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def io_to_numpy(t: torch.Tensor, io: str) -> np.ndarray:
+    """Host tensor -> the array type the oracle takes for that element type (bfloat16 travels as uint16 bits)."""
+    if io == "bf16":
+        return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def decode16(a: np.ndarray, io: str) -> np.ndarray:
+    """16-bit float array (float16, or uint16 holding bfloat16 bits) -> float64 values."""
+    if io == "bf16":
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def ulp16_distance(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Distance in units of the last place between two arrays of 16-bit float bit patterns (binary16 or bfloat16;
+    sign-magnitude ordering is the same for both), finite values."""
+    def ordered(x):
+        u = x.view(np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7FFF), u)
+    return np.abs(ordered(a) - ordered(b))
+
+
 def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor, tabs, state_np: np.ndarray,
                idx: torch.Tensor, off: torch.Tensor, gout: torch.Tensor, ws: torch.Tensor, check_sorted: bool = True,
-               same_inputs: bool = True):
+               same_inputs: bool = True, index_dtype: torch.dtype = torch.int64, io: str = "f32"):
     """One forward + backward on both sides, in place; compares everything.  Returns a dict of error figures.
     same_inputs: both sides start this step from bit-identical weights (true for the first step).  After a
     step on fp16 tables the two sides may already differ by one binary16 ulp where the fp32 and fp64 results
     straddle a rounding boundary, so later steps are held to the fp16 tolerance only."""
     B = cfg.B
-    idx_np, off_np, go_np = idx.numpy(), off.numpy(), gout.numpy()
-    d_idx, d_off, d_go = idx.cuda(), off.cuda(), gout.cuda()
+    extended = (index_dtype != torch.int64) or (io != "f32")     # the *_ex entry points
+    gout = gout.to(_IO_TORCH[io])                                 # both sides receive the same rounded gradient
+    idx_np, off_np, go_np = idx.numpy(), off.numpy(), io_to_numpy(gout, io)
+    d_idx, d_off, d_go = idx.to(index_dtype).cuda(), off.to(index_dtype).cuda(), gout.cuda()
     w_scale = cfg.w_scale
     report = {}
 
     # ---- forward
-    out_ref = oracle.forward(tabs, idx_np, off_np, B, cfg.pooling)
-    out_gpu = tbe.forward(flat, d_idx, d_off, B, cfg.pooling).cpu().numpy()
+    out_ref = oracle.forward(tabs, idx_np, off_np, B, cfg.pooling, out_dtype=io)
+    if extended:
+        out_gpu = io_to_numpy(tbe.forward_ex(flat, d_idx, d_off, B, cfg.pooling, out_dtype=_IO_TORCH[io]).cpu(), io)
+    else:
+        out_gpu = tbe.forward(flat, d_idx, d_off, B, cfg.pooling).cpu().numpy()
     assert not tbe.poll_index_error()
     fwd_rtol = RTOL_F32 if (cfg.weight_dtype == "f32" or same_inputs) else RTOL_F16
-    report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, w_scale, "forward")
+    if io == "f32":
+        report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, w_scale, "forward")
+    else:
+        # 16-bit output: the fp32 sum is rounded once.  Values: the fp32 tolerance plus one unit in the last place
+        # of the format.  Where the sum did not cancel (|ref| >= scale/10, so the fp32 error is far below the
+        # format's spacing) the result is the oracle's value or, rarely, its neighbour.
+        ulp_rel = 2.0 ** -10 if io == "f16" else 2.0 ** -7
+        ref64 = decode16(out_ref, io)
+        report["fwd_max_err"] = assert_close(decode16(out_gpu, io), ref64, fwd_rtol + ulp_rel, w_scale, "forward")
+        if same_inputs:
+            big = np.abs(ref64) >= 0.1 * w_scale
+            d = ulp16_distance(out_gpu, out_ref)[big]
+            if d.size:
+                assert d.max() <= 1, f"{io} forward: {int(d.max())} ulps from the oracle"
+                assert (d > 0).sum() <= max(2, 2e-3 * d.size), f"{int((d > 0).sum())}/{d.size} {io} outputs round differently"
+                report["fwd_ulp_mismatch_frac"] = float((d > 0).mean())
 
     # ---- backward + optimizer
     prev_tabs = split_flat(flat.cpu().numpy(), cfg)      # the GPU's own weights and moments before the step
     prev_state = state.cpu().numpy()
-    res = oracle.backward_rowwise_adagrad(tabs, state_np, go_np, idx_np, off_np, B, cfg.pooling, cfg.lr, cfg.eps, cfg.c)
-    tbe.backward_rowwise_adagrad(d_go, d_idx, d_off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
-                                 momentum_scale=cfg.c)
+    res = oracle.backward_rowwise_adagrad(tabs, state_np, go_np, idx_np, off_np, B, cfg.pooling, cfg.lr, cfg.eps, cfg.c,
+                                          grad_dtype=io)
+    step_fn = tbe.backward_rowwise_adagrad_ex if extended else tbe.backward_rowwise_adagrad
+    step_fn(d_go, d_idx, d_off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
     assert not tbe.poll_index_error()
     nnz = idx.numel()
     if check_sorted and nnz > 0:
@@ -127,7 +174,8 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
     return report
 
 
-def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_sorted: bool = True):
+def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_sorted: bool = True,
+               index_dtype: torch.dtype = torch.int64, io: str = "f32"):
     tabs = host_tables(cfg)
     flat = flat_from_tables(tabs)
     state_np = np.zeros(cfg.total_rows, dtype=np.float32)
@@ -141,6 +189,6 @@ def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_s
         gout = W.make_grad_out(cfg, step)
         ws = tbe.alloc_workspace(cfg.B, max(1, idx.numel()))
         reports.append(check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws, check_sorted,
-                                  same_inputs=(step == 0)))
+                                  same_inputs=(step == 0), index_dtype=index_dtype, io=io))
     tbe.close()
     return reports

@@ -325,3 +325,68 @@ def test_fp16_tables_round_once_to_nearest_even(oracle_mod):
     exact = w0[0].astype(np.float64) - 0.01 / (math.sqrt(1.0 + g @ g) + 1e-8) * g
     assert np.array_equal(tab[0].view(np.uint16), exact.astype(np.float16).view(np.uint16))
     assert np.array_equal(tab[1].view(np.uint16), w0[1].view(np.uint16))
+
+
+# ---- 16-bit element types of the pooled output and of the upstream gradient ------------------------------------
+def test_bf16_conversions_match_truncated_binary32(oracle_mod):
+    # every finite bfloat16 pattern decodes to the binary32 value whose upper half it is
+    bits = np.arange(0, 1 << 16, dtype=np.uint32)
+    as_f32 = (bits << 16).astype(np.uint32).view(np.float32)
+    for b in list(range(0, 1 << 16, 37)) + [0x0001, 0x007F, 0x0080, 0x7F7F, 0x8001, 0xFF7F]:
+        x = oracle_mod.bf16_to_double(b)
+        if np.isnan(as_f32[b]):
+            assert math.isnan(x)
+        else:
+            assert x == float(as_f32[b]), hex(b)
+    # encoding: against the library's float32 -> bfloat16 (round to nearest even) on values exact in binary32
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([rng.standard_normal(3000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 3000),
+                         np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 3.4e38, 1e-40, 9.2e-41,
+                                   4.6e-41, 4.5e-41, np.inf, -np.inf], dtype=np.float32)]).astype(np.float32)
+    want = torch.from_numpy(xs).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for x, w in zip(xs, want):
+        assert oracle_mod.double_to_bf16(float(x)) == int(w), (float(x), hex(int(w)))
+    # ties go to the even mantissa: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert oracle_mod.double_to_bf16(1.0 + 2.0 ** -8) == 0x3F80
+    assert oracle_mod.double_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82
+    # a double just above the tie rounds up although binary32 would first round it onto the tie
+    assert oracle_mod.double_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81
+
+
+def test_16bit_output_is_the_fp64_sum_rounded_once(oracle_mod):
+    rng = np.random.default_rng(11)
+    B = 6
+    tabs, idx, off = tiny_problem(rng, T=3, B=B, maxL=5, Rs=(9, 4, 6), Ds=(4, 2, 3))
+    # exact fp64 pooled sums, from the dense count-matrix form
+    exact = np.concatenate([count_matrix(t, tabs[t].shape[0], idx, off, B, "sum") @ tabs[t].astype(np.float64)
+                            for t in range(3)], axis=1)
+    o16 = oracle_mod.forward(tabs, idx, off, B, "sum", out_dtype="f16")
+    want16 = torch.from_numpy(exact).to(torch.float16).numpy()      # float64 -> binary16 in one rounding
+    assert np.array_equal(o16.view(np.uint16), want16.view(np.uint16))
+    ob = oracle_mod.forward(tabs, idx, off, B, "sum", out_dtype="bf16")
+    back = np.array([oracle_mod.bf16_to_double(int(b)) for b in ob.reshape(-1)]).reshape(exact.shape)
+    # nearest bfloat16: within half a unit in the last place (2^-8 relative), and exactly representable
+    assert np.all(np.abs(back - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-300)
+    assert np.array_equal((back.astype(np.float32).view(np.uint32) & 0xFFFF), np.zeros(exact.shape, dtype=np.uint32))
+
+
+@pytest.mark.parametrize("io", ["f16", "bf16"])
+def test_16bit_gradient_equals_its_exact_float32_image(oracle_mod, io):
+    # a 16-bit upstream gradient converts to float32 without error, so the step must equal the float32 step
+    rng = np.random.default_rng(13)
+    B = 6
+    tabs, idx, off = tiny_problem(rng, T=3, B=B, maxL=5, Rs=(9, 4, 6), Ds=(4, 2, 3))
+    sumD = sum(a.shape[1] for a in tabs)
+    g32 = torch.from_numpy(rng.standard_normal((B, sumD)).astype(np.float32))
+    g16 = g32.to(torch.float16 if io == "f16" else torch.bfloat16)
+    g16_np = g16.numpy() if io == "f16" else g16.view(torch.int16).numpy().view(np.uint16)
+    ta, tb = [a.copy() for a in tabs], [a.copy() for a in tabs]
+    va = np.zeros(sum(a.shape[0] for a in tabs), dtype=np.float32)
+    vb = va.copy()
+    ra = oracle_mod.backward_rowwise_adagrad(ta, va, g16_np, idx, off, B, "mean", 0.05, 1e-8, 2.0, grad_dtype=io)
+    rb = oracle_mod.backward_rowwise_adagrad(tb, vb, g16.to(torch.float32).numpy(), idx, off, B, "mean", 0.05, 1e-8, 2.0)
+    assert ra.U == rb.U and ra.U > 0
+    for a, b in zip(ta, tb):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.array_equal(va.view(np.uint32), vb.view(np.uint32))
+    assert not np.array_equal(ta[0], tabs[0])
