@@ -46,6 +46,7 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.unit_list = take(8 * (size_t)w.cap_units);
     w.bounds = take(4 * (size_t)(kMaxSlices + 1) * (size_t)w.cap_long);
     w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
+    w.tickets = take(4 * (size_t)kTicketWords);   // directly behind long_tables: one loop clears both
     w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);

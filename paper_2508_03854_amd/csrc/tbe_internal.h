@@ -20,6 +20,8 @@ constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous s
 constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
+constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
+constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
 constexpr int kCounterWords = 64;      // device counters: [0]=U [1]=long rows [2]=partial slots [3]=units [4]=long rows noted
 
 struct TimingSlot {
@@ -58,8 +60,8 @@ namespace tbe {
 struct Workspace {
     // keys/vals: radix double buffers of N+1 words each.  After the sort the buffer pair that does not hold the
     // result is reused: keys[spare] <- bag id of every sorted position, vals[spare] <- unique_rows.
-    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, raw_long, long_list,
-        unit_list, bounds, partial, total;
+    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, raw_long,
+        long_list, unit_list, bounds, partial, total;
     int radix_blocks;     // G
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;

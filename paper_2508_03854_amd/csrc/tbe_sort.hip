@@ -355,7 +355,7 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
                                                         const int64_t N, uint32_t* __restrict__ seg_start,
                                                         uint32_t* __restrict__ counters, uint32_t* __restrict__ zero,
                                                         const int zero_words) {
-    for (int i = threadIdx.x; i < zero_words; i += 1024) zero[i] = 0u;  // per-table long-row counters
+    for (int i = threadIdx.x; i < zero_words; i += 1024) zero[i] = 0u;  // per-table long-row counters, unit tickets
     __shared__ uint32_t smem[1024 / kWave];
     uint32_t carry = 0;
     for (int base = 0; base < nblocks; base += 1024) {
@@ -451,7 +451,8 @@ hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws,
     {
         LaunchTimer tm(h, s, "rle_scan");
         rle_scan_kernel<<<1, 1024, 0, s>>>(counts, w.rle_blocks, N, seg_start, counters,
-                                           reinterpret_cast<uint32_t*>(ws + w.long_tables), 3 * (h->T + 1));
+                                           reinterpret_cast<uint32_t*>(ws + w.long_tables),
+                                           (int)((w.tickets - w.long_tables) / 4) + kTicketWords);
         tm.done();
     }
     {
