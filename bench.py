@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--index-dtype", choices=["i64", "i32"], default="i64", help="ids and offsets (i32: *_ex calls)")
     ap.add_argument("--io", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of out and grad_out (16-bit: *_ex calls)")
+    ap.add_argument("--optimizer", choices=["rowwise_adagrad", "sgd"], default="rowwise_adagrad")
+    ap.add_argument("--momentum-scale", type=float, default=None, help="override the workload's scaling factor c")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -109,7 +111,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    cfg = W.config(args.workload, rows_scale=args.rows_scale)
+    cfg = W.config(args.workload, rows_scale=args.rows_scale,
+                   **({} if args.momentum_scale is None else {"c": args.momentum_scale}))
     log("workload:", W.describe(cfg), "" if args.rows_scale == 1.0 else f"[rows scaled by {args.rows_scale}]")
 
     # ---- inputs, generated directly in HBM
@@ -137,6 +140,10 @@ def main():
 
     def step(k):
         idx, off = batches[k % pool]
+        if args.optimizer == "sgd":
+            tbe.forward_ex(flat, idx, off, cfg.B, cfg.pooling, out=out)
+            tbe.backward_sgd(gouts[k % n_go], idx, off, cfg.B, flat, ws, pooling=cfg.pooling, lr=cfg.lr)
+            return
         if extended:
             tbe.forward_ex(flat, idx, off, cfg.B, cfg.pooling, out=out)
             tbe.backward_rowwise_adagrad_ex(gouts[k % n_go], idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling,
@@ -242,8 +249,9 @@ def main():
             t0 = time.perf_counter()
             for _ in range(reps):
                 oracle.forward(tabs, i_np, o_np, cfg.B, cfg.pooling, out_dtype=args.io)
-                oracle.backward_rowwise_adagrad(tabs, st, g_np, i_np, o_np, cfg.B, cfg.pooling, cfg.lr, cfg.eps, cfg.c,
-                                                want_indices=False, grad_dtype=args.io)
+                oracle.backward_rowwise_adagrad(tabs, None if args.optimizer == "sgd" else st, g_np, i_np, o_np, cfg.B,
+                                                cfg.pooling, cfg.lr, cfg.eps, cfg.c, want_indices=False,
+                                                grad_dtype=args.io)
             return time.perf_counter() - t0, int(i_np.size) * reps
 
         t1, n1 = run(1, 1)
@@ -270,7 +278,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": (f"{cfg.name}: " if args.rows_scale == 1.0 else f"{cfg.name} with rows x{args.rows_scale}: ")
                    + W.describe(cfg), "weight_dtype": cfg.weight_dtype, "index_dtype": args.index_dtype,
-                   "io_dtype": args.io,
+                   "io_dtype": args.io, "optimizer": args.optimizer,
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
                    "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c},

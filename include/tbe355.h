@@ -110,6 +110,24 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
                                            float momentum_scale, void* tables, float* state, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
 
+/* Same backward with the plain SGD step the paper names as the conventional alternative to row-wise AdaGrad
+ * (Section 3.2, first paragraph):  w_u -= lr * g  once per unique row, g the row's summed gradient as above.
+ * No optimizer state.  Same workspace, argument rules and determinism as the row-wise AdaGrad call. */
+tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,
+                            const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
+                            float lr, void* tables, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Replica synchronisation (Algorithm 1, the weight-sync and moment-sync steps after the local update) for M
+ * replicas that live on this one device:  x^(j) <- (1/M) * sum_m x^(m)  for every replica j, element by element.
+ * Call it once on the replicas' `tables` buffers (dtype of the handle) and once on their `state` buffers
+ * (TBE_F32).  Across devices this step is an all-reduce and is not part of this library.
+ *   replicas  HOST array of M DEVICE pointers (1 <= M <= 16), pairwise distinct, each 16-byte aligned, `count`
+ *             elements of `dtype`; read and overwritten in place
+ * The sum runs over the replicas in index order in fp32 and is divided by M; binary16 buffers are rounded once,
+ * to nearest even.  M == 1 leaves the buffer untouched.  TBE_EINVAL for a null, misaligned or repeated pointer. */
+tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, size_t count, tbe_dtype dtype,
+                            void* hip_stream);
+
 /* Parity hooks: DEVICE pointers into `workspace` holding the integer by-products of the last backward
  * call made with the same (h, workspace, B, nnz); valid until the next backward on that workspace.
  *   keys_sorted[nnz], vals_sorted[nnz] (original positions p, ascending inside a run of equal keys),

@@ -57,6 +57,8 @@ def lib():
                                                          ctypes.c_void_p, ctypes.c_int, i64p, i64p, ctypes.c_int32,
                                                          ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                                          i64p, i64p, i64p, i64p]
+        L.oracle_replica_mean.restype = None
+        L.oracle_replica_mean.argtypes = [vpp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int]
         L.oracle_forward_bag.restype = ctypes.c_int
         L.oracle_forward_bag.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int32, i64p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int, f32p]
@@ -232,7 +234,8 @@ def backward_rowwise_adagrad(tables: List[np.ndarray], state: np.ndarray, grad_o
     dt, rows, D, ptrs = _tables(tables)
     indices, offsets = _i64(indices), _i64(offsets)
     N = indices.shape[0]
-    assert state.dtype == np.float32 and state.shape == (int(rows.sum()),) and state.flags["C_CONTIGUOUS"]
+    if state is not None:     # None: plain SGD step (backward_sgd)
+        assert state.dtype == np.float32 and state.shape == (int(rows.sum()),) and state.flags["C_CONTIGUOUS"]
     want_np = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[grad_dtype]
     assert grad_out.dtype == want_np and grad_out.shape == (B, int(D.sum())) and grad_out.flags["C_CONTIGUOUS"]
     assert offsets.shape[0] == len(tables) * B + 1 and offsets[-1] == N
@@ -248,7 +251,9 @@ def backward_rowwise_adagrad(tables: List[np.ndarray], state: np.ndarray, grad_o
         return _p(a, ctypes.c_int64) if a is not None else null
 
     U = lib().oracle_backward_rowwise_adagrad_io(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
-                                                 _p(state, ctypes.c_float), grad_out.ctypes.data, _IO[grad_dtype],
+                                                 _p(state, ctypes.c_float) if state is not None
+                                                 else ctypes.POINTER(ctypes.c_float)(),
+                                                 grad_out.ctypes.data, _IO[grad_dtype],
                                                  _p(indices, ctypes.c_int64), _p(offsets, ctypes.c_int64), B,
                                                  _pooling(pooling), float(lr), float(eps), float(c),
                                                  ptr(ks), ptr(order), ptr(uniq), ptr(seg))
@@ -261,3 +266,24 @@ def backward_rowwise_adagrad(tables: List[np.ndarray], state: np.ndarray, grad_o
     else:
         res.keys_sorted = res.order = res.unique_rows = res.seg_start = None
     return res
+
+
+def backward_sgd(tables: List[np.ndarray], grad_out: np.ndarray, indices, offsets, B: int, pooling="sum",
+                 lr: float = 0.01, want_indices: bool = True, grad_dtype: str = "f32") -> BackwardResult:
+    """Same sparse backward with the plain SGD step w -= lr * g per unique row; in place on `tables`."""
+    return backward_rowwise_adagrad(tables, None, grad_out, indices, offsets, B, pooling, lr, 0.0, 1.0, want_indices,
+                                    grad_dtype)
+
+
+def replica_mean(replicas: Sequence[np.ndarray]) -> None:
+    """In place: every array (one per replica, same shape; float32, or float16/uint16 holding binary16) becomes the
+    element-wise mean over the replicas (Algorithm 1, weight sync and moment sync)."""
+    M = len(replicas)
+    assert M >= 1
+    first = replicas[0]
+    for a in replicas:
+        assert a.shape == first.shape and a.dtype == first.dtype and a.flags["C_CONTIGUOUS"]
+    code = F32 if first.dtype == np.float32 else F16
+    assert first.dtype in (np.float32, np.float16, np.uint16)
+    ptrs = (ctypes.c_void_p * M)(*[a.ctypes.data for a in replicas])
+    lib().oracle_replica_mean(ptrs, M, int(first.size), code)

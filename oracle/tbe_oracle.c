@@ -255,6 +255,15 @@ void oracle_adagrad_row(void* table, int dtype, int64_t r, int32_t D, float* v /
     *v = (float)v_new;
 }
 
+/* Plain SGD step of one row, the conventional optimizer the paper contrasts row-wise AdaGrad with
+ * (Section 3.2):  w <- w - eta * g.  No state. */
+void oracle_sgd_row(void* table, int dtype, int64_t r, int32_t D, const double* g, double lr) {
+    for (int32_t j = 0; j < D; ++j) {
+        double w = load_w(table, dtype, r * D + j);
+        store_w(table, dtype, r * D + j, w - lr * g[j]);
+    }
+}
+
 /* Row gradient straight from the definition, no sorting: scan every position of table t and add the
  * bag's upstream gradient slice (times the bag's pooling factor) whenever the id equals r.
  * grad_out is [B, sumD] row-major, doff = D_off[t].  Returns the number of hits. */
@@ -315,7 +324,8 @@ int64_t oracle_backward_rowwise_adagrad_io(int32_t T, const int64_t* rows, const
                 double s = bag_scale(offsets, bag, pooling);
                 for (int32_t j = 0; j < Dt; ++j) g[j] += s * load_io(grad_out, grad_io, b * sumD + doff + j);
             }
-            oracle_adagrad_row(tables[t], dtype, r, Dt, &state[uniq[u]], g, lr, eps, c);
+            if (state) oracle_adagrad_row(tables[t], dtype, r, Dt, &state[uniq[u]], g, lr, eps, c);
+            else oracle_sgd_row(tables[t], dtype, r, Dt, g, lr);      /* state == NULL: plain SGD */
         }
         if (keys_sorted_out) memcpy(keys_sorted_out, ks, (size_t)N * sizeof(int64_t));
         if (order_out) memcpy(order_out, order, (size_t)N * sizeof(int64_t));
@@ -334,4 +344,17 @@ int64_t oracle_backward_rowwise_adagrad(int32_t T, const int64_t* rows, const in
     return oracle_backward_rowwise_adagrad_io(T, rows, D, dtype, tables, state, grad_out, ORACLE_IO_F32, indices, offsets,
                                               B, pooling, lr, eps, c, keys_sorted_out, order_out, unique_rows_out,
                                               seg_start_out);
+}
+
+/* ---- cross-replica synchronisation (Algorithm 1, the weight-sync and moment-sync steps) -----------------
+ * Every replica m = 0..M-1 holds its own copy of a buffer (weights of one table set, or the moments); after the
+ * step each copy is replaced by the element-wise mean over the replicas,  x^(j) <- (1/M) sum_m x^(m)  for all j.
+ * dtype: ORACLE_F32 or ORACLE_F16 (the mean is formed in fp64 and rounded once to the storage type). */
+void oracle_replica_mean(void* const* replicas, int32_t M, int64_t count, int dtype) {
+    for (int64_t e = 0; e < count; ++e) {
+        double sum = 0.0;
+        for (int32_t m = 0; m < M; ++m) sum += load_w(replicas[m], dtype, e);
+        double mean = sum / (double)M;
+        for (int32_t m = 0; m < M; ++m) store_w(replicas[m], dtype, e, mean);
+    }
 }

@@ -23,7 +23,7 @@ _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
-           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex",
+           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_sgd", "tbe_replica_mean",
            "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable", "tbe_timing_count", "tbe_timing_read",
            "tbe_calibration_copy", "tbe_status_string"]
 
@@ -66,6 +66,11 @@ def load_library():
     L.tbe_backward_rowwise_adagrad_ex.restype = ctypes.c_int
     L.tbe_backward_rowwise_adagrad_ex.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int,
                                                   f32, f32, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    L.tbe_backward_sgd.restype = ctypes.c_int
+    L.tbe_backward_sgd.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int, f32, vp, vp,
+                                   ctypes.c_size_t, vp]
+    L.tbe_replica_mean.restype = ctypes.c_int
+    L.tbe_replica_mean.argtypes = [vp, ctypes.POINTER(vp), i32, ctypes.c_size_t, ctypes.c_int, vp]
     L.tbe_debug_sorted.restype = ctypes.c_int
     L.tbe_debug_sorted.argtypes = [vp, vp, i32, i64] + [ctypes.POINTER(vp)] * 5
     L.tbe_poll_index_error.restype = ctypes.c_int
@@ -223,6 +228,25 @@ class TBE:
             _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
         _check(st, "tbe_backward_rowwise_adagrad_ex")
 
+    # ---- tbe_backward_sgd
+    def backward_sgd(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,
+                     tables: torch.Tensor, workspace: torch.Tensor, *, pooling: str = "sum", lr: float,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+        if tables.numel() != self.total_elems:
+            raise ValueError("tables shape does not match the handle")
+        if grad_out.shape != (B, self.sum_D) or offsets.numel() != self.T * B + 1:
+            raise ValueError("grad_out / offsets shape does not match the handle")
+        if grad_out.dtype not in _IO:
+            raise TypeError(f"grad_out must be float32, float16 or bfloat16, got {grad_out.dtype}")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_backward_sgd(
+            self._h, _dev_ptr(grad_out, grad_out.dtype, "grad_out"), _IO[grad_out.dtype],
+            _dev_ptr(indices, indices.dtype, "indices"), _dev_ptr(offsets, offsets.dtype, "offsets"), idt, int(B),
+            int(indices.numel()), {"sum": SUM, "mean": MEAN}[pooling], float(lr),
+            _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(workspace, torch.uint8, "workspace"),
+            int(workspace.numel()), _stream_ptr(stream))
+        _check(st, "tbe_backward_sgd")
+
     # ---- tbe_backward_rowwise_adagrad
     def backward_rowwise_adagrad(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,
                                  tables: torch.Tensor, state: torch.Tensor, workspace: torch.Tensor, *,
@@ -240,6 +264,20 @@ class TBE:
             _dev_ptr(state, torch.float32, "state"), _dev_ptr(workspace, torch.uint8, "workspace"),
             int(workspace.numel()), _stream_ptr(stream))
         _check(st, "tbe_backward_rowwise_adagrad")
+
+    # ---- tbe_replica_mean
+    def replica_mean(self, replicas: Sequence[torch.Tensor], stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Every tensor (one per replica, same shape; float32 or float16) becomes the element-wise mean."""
+        first = replicas[0]
+        if first.dtype not in (torch.float32, torch.float16):
+            raise TypeError(f"replicas must be float32 or float16, got {first.dtype}")
+        for r in replicas:
+            if r.dtype != first.dtype or r.numel() != first.numel():
+                raise ValueError("replicas must agree in dtype and size")
+        ptrs = (ctypes.c_void_p * len(replicas))(*[_dev_ptr(r, first.dtype, "replica") for r in replicas])
+        st = self._lib.tbe_replica_mean(self._h, ptrs, len(replicas), first.numel(),
+                                        F32 if first.dtype == torch.float32 else F16, _stream_ptr(stream))
+        _check(st, "tbe_replica_mean")
 
     # ---- tbe_debug_sorted
     def debug_sorted(self, workspace: torch.Tensor, B: int, nnz: int) -> Dict[str, torch.Tensor]:

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtbe355.so")
-SOURCES = ["tbe_api.hip", "tbe_forward.hip", "tbe_sort.hip", "tbe_backward.hip"]
+SOURCES = ["tbe_api.hip", "tbe_forward.hip", "tbe_sort.hip", "tbe_backward.hip", "tbe_sync.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -219,12 +219,12 @@ tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D
     return tbe_forward_ex(h, tables, D_offsets, indices, offsets, TBE_I64, B, nnz, pooling, out, TBE_IO_F32, hip_stream);
 }
 
-tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
-                                           const void* indices, const void* offsets, tbe_index_dtype index_dtype,
-                                           int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
-                                           float momentum_scale, void* tables, float* state, void* workspace,
-                                           size_t workspace_bytes, void* hip_stream) {
-    if (!h || !grad_out || !offsets || !tables || !state || (!indices && nnz > 0)) return TBE_EINVAL;
+// shared body of the backward entry points; state == nullptr selects the plain SGD step
+static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,
+                                const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz,
+                                tbe_pooling pooling, float lr, float eps, float momentum_scale, void* tables, float* state,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!h || !grad_out || !offsets || !tables || (!indices && nnz > 0)) return TBE_EINVAL;
     if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
     if (!io_ok(grad_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
     if (!isfinite(lr) || !isfinite(eps) || eps < 0.f || !isfinite(momentum_scale) || !(momentum_scale > 0.f))
@@ -253,6 +253,23 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
     e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, (int)grad_dtype, offsets, idx32, B, pooling, lr, eps,
                               momentum_scale, tables, state, s);
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                           const void* indices, const void* offsets, tbe_index_dtype index_dtype,
+                                           int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
+                                           float momentum_scale, void* tables, float* state, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
+    if (!state) return TBE_EINVAL;
+    return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
+                         tables, state, workspace, workspace_bytes, hip_stream);
+}
+
+tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,
+                            const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
+                            float lr, void* tables, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, 0.f, 1.f, tables,
+                         nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
@@ -301,6 +318,20 @@ tbe_status tbe_calibration_copy(tbe_handle* h, void* dst, const void* src, size_
     calibration_copy_kernel<<<256 * 16, 256, 0, s>>>(static_cast<float4*>(dst), static_cast<const float4*>(src), bytes / 16);
     tm.done();
     return hipGetLastError() == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, size_t count, tbe_dtype dtype,
+                            void* hip_stream) {
+    if (!h || !replicas || M < 1 || M > kMaxReplicas) return TBE_EINVAL;
+    if (dtype != TBE_F32 && dtype != TBE_F16) return TBE_EDTYPE;
+    for (int m = 0; m < M; ++m) {
+        if (!replicas[m] || !aligned(replicas[m], 16)) return TBE_EINVAL;
+        for (int k = 0; k < m; ++k)
+            if (replicas[k] == replicas[m]) return TBE_EINVAL;   // two replicas in one buffer would race
+    }
+    if (count == 0 || M == 1) return TBE_OK;   // the mean over one replica is that replica
+    const hipError_t e = launch_replica_mean(h, replicas, M, count, dtype == TBE_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
 tbe_status tbe_timing_enable(tbe_handle* h, int enable) {

@@ -70,7 +70,7 @@ struct SegArgs {
     uint32_t total_rows;
     float lr, eps, inv_c;
     void* tables;
-    float* state;
+    float* state;          // nullptr: plain SGD step, no moments
     uint32_t* long_list;   // [cap_long][4]  (u, first slot, parts | sliced flag, table)
     float* partial;        // [cap_chunks][maxD] partial sums of long rows
     uint2* raw_long;       // [cap_long] long rows in arrival order (u, table), written by the row-update kernel
@@ -157,10 +157,11 @@ __device__ __forceinline__ void fold_groups(float (&acc)[NC][4], const RowGeom& 
 // marks (all groups after fold_groups, or each group its own row).  v_old is the row's moment.
 //   v <- v + ||g||^2 ;  w <- w - lr / (sqrt(v / c) + eps) * g      (updated v; v stored unscaled)
 // Lanes with write == true store their 4 columns; the lane with lc == 0 among them stores the moment.
+// With sgd == true the step is plain SGD instead, w <- w - lr * g, and the moment is neither read nor written.
 template <typename WT, int NC>
 __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const RowGeom& g, WT* __restrict__ wrow,
                                             float* __restrict__ vptr, const float v_old, const bool write,
-                                            const float lr, const float eps, const float inv_c) {
+                                            const float lr, const float eps, const float inv_c, const bool sgd = false) {
     float sq = 0.f;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -173,7 +174,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
     for (int o = 1; o < g.LPR; o <<= 1) sq += __shfl_xor(sq, o, kWave);  // within the LPR lanes that cover the row
     const float v_new = v_old + sq;
     const float denom = sqrtf(v_new * inv_c) + eps;
-    const float step = v_new > 0.f ? lr / denom : 0.f;  // v_new == 0 means g == 0: nothing to apply
+    const float step = sgd ? lr : (v_new > 0.f ? lr / denom : 0.f);  // v_new == 0 means g == 0: nothing to apply
     if (write) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -186,7 +187,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
                 RowIO<WT>::store4(wrow + col, w);
             }
         }
-        if (g.lc == 0) *vptr = v_new;
+        if (g.lc == 0 && !sgd) *vptr = v_new;
     }
 }
 
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
         if (live) {
             t = table_of_key(a.row_base, a.T, key);
             D = a.D_off[t + 1] - a.D_off[t];
-            v = a.state[key];
+            v = a.state ? a.state[key] : 0.f;
         }
         int r = 0;
         while (r < (int)rpw) {
@@ -509,7 +510,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                                         a.offsets, s_r, s_r + len_r);
                 fold_groups<1>(acc, g);
                 WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
-                adagrad_row<WT, 1>(acc, g, wrow, a.state + key_r, v_r, g.sub == 0, a.lr, a.eps, a.inv_c);
+                adagrad_row<WT, 1>(acc, g, wrow, a.state + key_r, v_r, g.sub == 0, a.lr, a.eps, a.inv_c, a.state == nullptr);
                 ++r;
                 continue;
             }
@@ -573,7 +574,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                     }
                 }
             }
-            adagrad_row<WT, 1>(acc, g, wrow, a.state + gkey, gv, gon, a.lr, a.eps, a.inv_c);
+            adagrad_row<WT, 1>(acc, g, wrow, a.state + gkey, gv, gon, a.lr, a.eps, a.inv_c, a.state == nullptr);
             r += k;
         }
     }
@@ -604,7 +605,8 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         segment_reduce<4, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + d0, a.sumD, (int64_t)t * a.B, a.bag_sorted,
                                     a.offsets, s, e);
         fold_groups<4>(acc, g);
-        adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], g.sub == 0, a.lr, a.eps, a.inv_c);
+        adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state ? a.state[key] : 0.f, g.sub == 0, a.lr, a.eps, a.inv_c,
+                           a.state == nullptr);
     }
 }
 
@@ -663,7 +665,8 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
                 }
             }
             WT* wrow = tables + a.w_off[t] + ((int64_t)key - a.row_base[t]) * D;
-            adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state[key], true, a.lr, a.eps, a.inv_c);
+            adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state ? a.state[key] : 0.f, true, a.lr, a.eps, a.inv_c,
+                               a.state == nullptr);
         }
         __syncthreads();
     }

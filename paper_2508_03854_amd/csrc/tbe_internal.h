@@ -20,6 +20,7 @@ constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous s
 constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
+constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
 constexpr int kCounterWords = 64;      // device counters: [0]=U [1]=long rows [2]=partial slots [3]=units [4]=long rows noted
@@ -83,6 +84,8 @@ struct LaunchTimer {
 hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const void* indices,
                           const void* offsets, int idx32, int32_t B, int64_t nnz, tbe_pooling pooling, void* out,
                           int out_io, hipStream_t s);
+// every replicas[m] (device pointers, M <= kMaxReplicas) becomes the element-wise mean; count elements each
+hipError_t launch_replica_mean(const tbe_handle* h, void* const* replicas, int M, size_t count, bool f32, hipStream_t s);
 hipError_t launch_linearize(const tbe_handle* h, const void* indices, const void* offsets, int idx32, int32_t B, int64_t N,
                             uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s);
 // sorts keys[0] of the workspace with the positions 0..N-1 as payload; returns in *result_buf which buffer pair

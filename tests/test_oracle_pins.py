@@ -390,3 +390,48 @@ def test_16bit_gradient_equals_its_exact_float32_image(oracle_mod, io):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
     assert np.array_equal(va.view(np.uint32), vb.view(np.uint32))
     assert not np.array_equal(ta[0], tabs[0])
+
+
+# ---- plain SGD variant -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("pooling", ["sum", "mean"])
+def test_sgd_equals_dense_gradient_step(oracle_mod, pooling):
+    # the gradient of the pooled output with respect to the table is P^T . grad_out; SGD subtracts lr times it
+    rng = np.random.default_rng(21)
+    B = 5
+    tables, idx, offsets = tiny_problem(rng)
+    sumD = sum(a.shape[1] for a in tables)
+    go = rng.standard_normal((B, sumD)).astype(np.float32)
+    new = [a.copy() for a in tables]
+    res = oracle_mod.backward_sgd(new, go, idx, offsets, B, pooling, lr=0.3)
+    col = 0
+    touched = 0
+    for t, Wt in enumerate(tables):
+        P = count_matrix(t, Wt.shape[0], idx, offsets, B, pooling)
+        dense = Wt.astype(np.float64) - 0.3 * (P.T @ go[:, col:col + Wt.shape[1]].astype(np.float64))
+        np.testing.assert_allclose(new[t], dense, rtol=1e-6, atol=1e-7)
+        hit = P.sum(axis=0) > 0
+        assert np.array_equal(new[t][~hit].view(np.uint32), Wt[~hit].view(np.uint32))     # untouched rows keep their bits
+        touched += int(hit.sum())
+        col += Wt.shape[1]
+    assert res.U == touched
+
+
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_sgd_matches_library_embedding_bag_with_sgd(oracle_mod, mode):
+    rng = np.random.default_rng(22)
+    R, D, B = 11, 6, 7
+    W0 = rng.standard_normal((R, D)).astype(np.float32)
+    lens = rng.integers(0, 5, size=B)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    go = rng.standard_normal((B, D)).astype(np.float32)
+    emb = torch.nn.EmbeddingBag(R, D, mode=mode, sparse=False)
+    with torch.no_grad():
+        emb.weight.copy_(torch.from_numpy(W0))
+    opt = torch.optim.SGD(emb.parameters(), lr=0.25)
+    out = emb(torch.from_numpy(idx), torch.from_numpy(off[:-1]))
+    out.backward(torch.from_numpy(go))
+    opt.step()
+    mine = [W0.copy()]
+    oracle_mod.backward_sgd(mine, go, idx, off, B, mode, lr=0.25)
+    np.testing.assert_allclose(mine[0], emb.weight.detach().numpy(), rtol=1e-5, atol=1e-6)
