@@ -117,6 +117,28 @@ tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dt
                             const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
                             float lr, void* tables, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Non-pooled lookup and its backward (Section 2.1: the forward maps categorical ids to embedding rows; this is
+ * that map without pooling, as needed by features that are a long sequence of event ids per sample).
+ *   offsets  DEVICE [T+1], ascending from 0 to nnz: the ids of table t are indices[offsets[t] .. offsets[t+1])
+ *            (this is the pooled layout with B = 1); same element type as indices
+ *   out / grad_seq  DEVICE, 16-byte aligned: one row-major [n_t, D_t] block per table, n_t = offsets[t+1]-offsets[t],
+ *            the blocks one after the other (a single [nnz, D] matrix when all tables have the same D);
+ *            out_elems / grad_elems = number of elements the caller's buffer holds, >= sum_t n_t * D_t
+ * tbe_lookup_seq:  out row of position p = W_t[indices[p], :], converted to out_dtype (one rounding).
+ * tbe_backward_seq_rowwise_adagrad: as tbe_backward_rowwise_adagrad_ex with the row gradient
+ *   g = sum over the positions p that hold the row's id of grad_seq row p;  workspace >= tbe_workspace_bytes(h, 1, nnz).
+ * An id outside its table reads as a zero row in the lookup, gets no update in the backward, and is reported by
+ * tbe_poll_index_error; so is an offsets array that is not ascending from 0 to nnz or does not fit the buffer (the
+ * lookup then skips the affected rows, the backward updates nothing). */
+tbe_status tbe_lookup_seq(const tbe_handle* h, const void* tables, const void* indices, const void* offsets,
+                          tbe_index_dtype index_dtype, int64_t nnz, void* out, tbe_io_dtype out_dtype, int64_t out_elems,
+                          void* hip_stream);
+tbe_status tbe_backward_seq_rowwise_adagrad(const tbe_handle* h, const void* grad_seq, tbe_io_dtype grad_dtype,
+                                            int64_t grad_elems, const void* indices, const void* offsets,
+                                            tbe_index_dtype index_dtype, int64_t nnz, float lr, float eps,
+                                            float momentum_scale, void* tables, float* state, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream);
+
 /* Replica synchronisation (Algorithm 1, the weight-sync and moment-sync steps after the local update) for M
  * replicas that live on this one device:  x^(j) <- (1/M) * sum_m x^(m)  for every replica j, element by element.
  * Call it once on the replicas' `tables` buffers (dtype of the handle) and once on their `state` buffers

@@ -57,6 +57,12 @@ def lib():
                                                          ctypes.c_void_p, ctypes.c_int, i64p, i64p, ctypes.c_int32,
                                                          ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                                          i64p, i64p, i64p, i64p]
+        L.oracle_lookup_seq_io.restype = ctypes.c_int
+        L.oracle_lookup_seq_io.argtypes = [ctypes.c_int32, i64p, i32p, ctypes.c_int, vpp, i64p, i64p, ctypes.c_void_p,
+                                           ctypes.c_int]
+        L.oracle_backward_seq_io.restype = ctypes.c_int64
+        L.oracle_backward_seq_io.argtypes = [ctypes.c_int32, i64p, i32p, ctypes.c_int, vpp, f32p, ctypes.c_void_p,
+                                             ctypes.c_int, i64p, i64p, ctypes.c_double, ctypes.c_double, ctypes.c_double]
         L.oracle_replica_mean.restype = None
         L.oracle_replica_mean.argtypes = [vpp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int]
         L.oracle_forward_bag.restype = ctypes.c_int
@@ -287,3 +293,41 @@ def replica_mean(replicas: Sequence[np.ndarray]) -> None:
     assert first.dtype in (np.float32, np.float16, np.uint16)
     ptrs = (ctypes.c_void_p * M)(*[a.ctypes.data for a in replicas])
     lib().oracle_replica_mean(ptrs, M, int(first.size), code)
+
+
+_IO_NP = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
+
+
+def lookup_seq(tables: Sequence[np.ndarray], indices, table_offsets, out_dtype="f32") -> np.ndarray:
+    """Non-pooled lookup.  Returns the flat output: one row-major [n_t, D_t] block per table, one after the other."""
+    dt, rows, D, ptrs = _tables(tables)
+    indices, table_offsets = _i64(indices), _i64(table_offsets)
+    assert table_offsets.shape[0] == len(tables) + 1 and table_offsets[-1] == indices.shape[0] and table_offsets[0] == 0
+    total = int(((table_offsets[1:] - table_offsets[:-1]) * D).sum())
+    out = np.zeros(max(total, 1), dtype=_IO_NP[out_dtype])
+    rc = lib().oracle_lookup_seq_io(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
+                                    _p(indices, ctypes.c_int64), _p(table_offsets, ctypes.c_int64), out.ctypes.data,
+                                    _IO[out_dtype])
+    if rc:
+        raise IndexError("id outside its table")
+    return out[:total]
+
+
+def backward_seq(tables: List[np.ndarray], state: Optional[np.ndarray], grad_seq: np.ndarray, indices, table_offsets,
+                 lr: float = 0.01, eps: float = 1e-8, c: float = 1.0, grad_dtype: str = "f32") -> int:
+    """Backward of the non-pooled lookup, in place on `tables` and `state` (None: plain SGD).  Returns the number of
+    rows updated."""
+    dt, rows, D, ptrs = _tables(tables)
+    indices, table_offsets = _i64(indices), _i64(table_offsets)
+    assert table_offsets.shape[0] == len(tables) + 1 and table_offsets[-1] == indices.shape[0] and table_offsets[0] == 0
+    total = int(((table_offsets[1:] - table_offsets[:-1]) * D).sum())
+    assert grad_seq.dtype == _IO_NP[grad_dtype] and grad_seq.size >= total and grad_seq.flags["C_CONTIGUOUS"]
+    if state is not None:
+        assert state.dtype == np.float32 and state.shape == (int(rows.sum()),)
+    U = lib().oracle_backward_seq_io(len(tables), _p(rows, ctypes.c_int64), _p(D, ctypes.c_int32), dt, ptrs,
+                                     _p(state, ctypes.c_float) if state is not None else ctypes.POINTER(ctypes.c_float)(),
+                                     grad_seq.ctypes.data, _IO[grad_dtype], _p(indices, ctypes.c_int64),
+                                     _p(table_offsets, ctypes.c_int64), float(lr), float(eps), float(c))
+    if U < 0:
+        raise IndexError("id outside its table")
+    return int(U)

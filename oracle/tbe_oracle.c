@@ -358,3 +358,60 @@ void oracle_replica_mean(void* const* replicas, int32_t M, int64_t count, int dt
         for (int32_t m = 0; m < M; ++m) store_w(replicas[m], dtype, e, mean);
     }
 }
+
+/* ---- non-pooled lookup (Section 2.1: the forward maps ids to embedding rows; no pooling) ------------------
+ * table_offsets[T+1] ascending from 0 to nnz: table t owns positions table_offsets[t] .. table_offsets[t+1]-1.
+ * out / grad_seq: one row-major [n_t, D_t] block per table, the blocks one after the other. */
+int oracle_lookup_seq_io(int32_t T, const int64_t* rows, const int32_t* D, int dtype, const void* const* tables,
+                         const int64_t* indices, const int64_t* table_offsets, void* out, int out_io) {
+    int64_t base = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        for (int64_t p = table_offsets[t]; p < table_offsets[t + 1]; ++p) {
+            int64_t r = indices[p];
+            if (r < 0 || r >= rows[t]) return -1;
+            for (int32_t j = 0; j < D[t]; ++j)
+                store_io(out, out_io, base + (p - table_offsets[t]) * D[t] + j, load_w(tables[t], dtype, r * D[t] + j));
+        }
+        base += (table_offsets[t + 1] - table_offsets[t]) * D[t];
+    }
+    return 0;
+}
+
+/* Backward of the non-pooled lookup with the same optimizer step: the gradient of row r of table t is the sum of
+ * grad_seq rows over the positions that hold r (Section 3.2's sum over the samples that hit the row), then
+ * Algorithm 1 steps 5-6 (or the SGD step when state is NULL).  Straight from the definition: the positions of each row are
+ * collected by a bucket pass and their gradient rows added in ascending position order.  Returns the number of rows updated, -1 on a bad id. */
+int64_t oracle_backward_seq_io(int32_t T, const int64_t* rows, const int32_t* D, int dtype, void* const* tables,
+                               float* state, const void* grad_seq, int grad_io, const int64_t* indices,
+                               const int64_t* table_offsets, double lr, double eps, double c) {
+    int64_t updated = 0, base = 0, row_base = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        int64_t s0 = table_offsets[t], s1 = table_offsets[t + 1];
+        for (int64_t p = s0; p < s1; ++p)
+            if (indices[p] < 0 || indices[p] >= rows[t]) return -1;
+        /* the positions of every row, in ascending order: count, prefix sum, fill (a bucket pass, no comparison sort) */
+        int64_t R = rows[t];
+        int64_t* start = (int64_t*)calloc((size_t)R + 1, sizeof(int64_t));
+        int64_t* fill = (int64_t*)calloc((size_t)R, sizeof(int64_t));
+        int64_t* where = (int64_t*)malloc((size_t)(s1 > s0 ? s1 - s0 : 1) * sizeof(int64_t));
+        double* g = (double*)malloc((size_t)D[t] * sizeof(double));
+        for (int64_t p = s0; p < s1; ++p) start[indices[p] + 1] += 1;
+        for (int64_t r = 0; r < R; ++r) start[r + 1] += start[r];
+        for (int64_t p = s0; p < s1; ++p) { int64_t r = indices[p]; where[start[r] + fill[r]++] = p; }
+        for (int64_t r = 0; r < R; ++r) {
+            if (start[r + 1] == start[r]) continue;             /* the id does not appear: no gradient, no update */
+            for (int32_t j = 0; j < D[t]; ++j) g[j] = 0.0;
+            for (int64_t i = start[r]; i < start[r + 1]; ++i) {
+                int64_t q = where[i];
+                for (int32_t j = 0; j < D[t]; ++j) g[j] += load_io(grad_seq, grad_io, base + (q - s0) * D[t] + j);
+            }
+            if (state) oracle_adagrad_row(tables[t], dtype, r, D[t], &state[row_base + r], g, lr, eps, c);
+            else oracle_sgd_row(tables[t], dtype, r, D[t], g, lr);
+            ++updated;
+        }
+        free(start); free(fill); free(where); free(g);
+        base += (s1 - s0) * D[t];
+        row_base += rows[t];
+    }
+    return updated;
+}

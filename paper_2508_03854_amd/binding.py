@@ -23,7 +23,7 @@ _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
-           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_sgd", "tbe_replica_mean",
+           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq", "tbe_backward_seq_rowwise_adagrad",
            "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable", "tbe_timing_count", "tbe_timing_read",
            "tbe_calibration_copy", "tbe_status_string"]
 
@@ -69,6 +69,11 @@ def load_library():
     L.tbe_backward_sgd.restype = ctypes.c_int
     L.tbe_backward_sgd.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int, f32, vp, vp,
                                    ctypes.c_size_t, vp]
+    L.tbe_lookup_seq.restype = ctypes.c_int
+    L.tbe_lookup_seq.argtypes = [vp, vp, vp, vp, ctypes.c_int, i64, vp, ctypes.c_int, i64, vp]
+    L.tbe_backward_seq_rowwise_adagrad.restype = ctypes.c_int
+    L.tbe_backward_seq_rowwise_adagrad.argtypes = [vp, vp, ctypes.c_int, i64, vp, vp, ctypes.c_int, i64, f32, f32, f32,
+                                                   vp, vp, vp, ctypes.c_size_t, vp]
     L.tbe_replica_mean.restype = ctypes.c_int
     L.tbe_replica_mean.argtypes = [vp, ctypes.POINTER(vp), i32, ctypes.c_size_t, ctypes.c_int, vp]
     L.tbe_debug_sorted.restype = ctypes.c_int
@@ -264,6 +269,41 @@ class TBE:
             _dev_ptr(state, torch.float32, "state"), _dev_ptr(workspace, torch.uint8, "workspace"),
             int(workspace.numel()), _stream_ptr(stream))
         _check(st, "tbe_backward_rowwise_adagrad")
+
+    # ---- tbe_lookup_seq
+    def lookup_seq(self, tables: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, out: torch.Tensor,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """offsets: [T+1]; out: flat tensor of >= sum_t n_t * D_t elements (float32, float16 or bfloat16)."""
+        if tables.numel() != self.total_elems or offsets.numel() != self.T + 1:
+            raise ValueError("tables / offsets shape does not match the handle")
+        if out.dtype not in _IO:
+            raise TypeError(f"out must be float32, float16 or bfloat16, got {out.dtype}")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_lookup_seq(self._h, _dev_ptr(tables, self.torch_dtype, "tables"),
+                                      _dev_ptr(indices, indices.dtype, "indices"),
+                                      _dev_ptr(offsets, offsets.dtype, "offsets"), idt, int(indices.numel()),
+                                      _dev_ptr(out, out.dtype, "out"), _IO[out.dtype], int(out.numel()),
+                                      _stream_ptr(stream))
+        _check(st, "tbe_lookup_seq")
+        return out
+
+    # ---- tbe_backward_seq_rowwise_adagrad
+    def backward_seq_rowwise_adagrad(self, grad_seq: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor,
+                                     tables: torch.Tensor, state: torch.Tensor, workspace: torch.Tensor, *, lr: float,
+                                     eps: float, momentum_scale: float = 1.0,
+                                     stream: Optional[torch.cuda.Stream] = None) -> None:
+        if tables.numel() != self.total_elems or state.numel() != self.total_rows or offsets.numel() != self.T + 1:
+            raise ValueError("tables / state / offsets shape does not match the handle")
+        if grad_seq.dtype not in _IO:
+            raise TypeError(f"grad_seq must be float32, float16 or bfloat16, got {grad_seq.dtype}")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_backward_seq_rowwise_adagrad(
+            self._h, _dev_ptr(grad_seq, grad_seq.dtype, "grad_seq"), _IO[grad_seq.dtype], int(grad_seq.numel()),
+            _dev_ptr(indices, indices.dtype, "indices"), _dev_ptr(offsets, offsets.dtype, "offsets"), idt,
+            int(indices.numel()), float(lr), float(eps), float(momentum_scale),
+            _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(state, torch.float32, "state"),
+            _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
+        _check(st, "tbe_backward_seq_rowwise_adagrad")
 
     # ---- tbe_replica_mean
     def replica_mean(self, replicas: Sequence[torch.Tensor], stream: Optional[torch.cuda.Stream] = None) -> None:

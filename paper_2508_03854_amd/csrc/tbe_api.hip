@@ -14,6 +14,7 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     Workspace w;
     memset(&w, 0, sizeof(w));
     const size_t n = (size_t)(N > 0 ? N : 1);
+    w.n = N;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -47,6 +48,7 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.bounds = take(4 * (size_t)(kMaxSlices + 1) * (size_t)w.cap_long);
     w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
     w.tickets = take(4 * (size_t)kTicketWords);   // directly behind long_tables: one loop clears both
+    w.seq_gbase = take(8 * (size_t)(h->T + 1));
     w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);
@@ -220,11 +222,13 @@ tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D
 }
 
 // shared body of the backward entry points; state == nullptr selects the plain SGD step
+// seq != 0: the non-pooled layout (B is 1, offsets has T+1 entries, grad_out holds grad_elems elements)
 static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,
                                 const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz,
                                 tbe_pooling pooling, float lr, float eps, float momentum_scale, void* tables, float* state,
-                                void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!h || !grad_out || !offsets || !tables || (!indices && nnz > 0)) return TBE_EINVAL;
+                                void* workspace, size_t workspace_bytes, void* hip_stream, int seq = 0,
+                                int64_t grad_elems = 0) {
+    if (!h || !offsets || !tables || ((!indices || !grad_out) && nnz > 0)) return TBE_EINVAL;
     if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
     if (!io_ok(grad_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
     if (!isfinite(lr) || !isfinite(eps) || eps < 0.f || !isfinite(momentum_scale) || !(momentum_scale > 0.f))
@@ -248,10 +252,10 @@ static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_i
     int buf = 0;
     e = launch_radix_sort(h, w, ws, nnz, &buf, s);
     if (e != hipSuccess) return TBE_EHIP;
-    e = launch_run_lengths(h, w, ws, buf, nnz, s);
+    e = launch_run_lengths(h, w, ws, buf, nnz, seq, s);
     if (e != hipSuccess) return TBE_EHIP;
     e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, (int)grad_dtype, offsets, idx32, B, pooling, lr, eps,
-                              momentum_scale, tables, state, s);
+                              momentum_scale, tables, state, seq, grad_elems, s);
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
@@ -263,6 +267,30 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
     if (!state) return TBE_EINVAL;
     return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
                          tables, state, workspace, workspace_bytes, hip_stream);
+}
+
+tbe_status tbe_lookup_seq(const tbe_handle* h, const void* tables, const void* indices, const void* offsets,
+                          tbe_index_dtype index_dtype, int64_t nnz, void* out, tbe_io_dtype out_dtype, int64_t out_elems,
+                          void* hip_stream) {
+    if (!h || !tables || !offsets || (!indices && nnz > 0) || (!out && out_elems > 0) || out_elems < 0) return TBE_EINVAL;
+    if (!io_ok(out_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
+    const tbe_status st = check_batch(h, 1, nnz);
+    if (st != TBE_OK) return st;
+    const size_t ia = index_dtype == TBE_I32 ? 4 : 8;
+    if (!aligned(tables, 16) || !aligned(out, 16) || !aligned(indices, ia) || !aligned(offsets, ia)) return TBE_EINVAL;
+    const hipError_t e = launch_lookup_seq(h, tables, indices, offsets, index_dtype == TBE_I32, nnz, out, (int)out_dtype,
+                                           out_elems, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_backward_seq_rowwise_adagrad(const tbe_handle* h, const void* grad_seq, tbe_io_dtype grad_dtype,
+                                            int64_t grad_elems, const void* indices, const void* offsets,
+                                            tbe_index_dtype index_dtype, int64_t nnz, float lr, float eps,
+                                            float momentum_scale, void* tables, float* state, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+    if (!state || grad_elems < 0) return TBE_EINVAL;
+    return backward_impl(h, grad_seq, grad_dtype, indices, offsets, index_dtype, 1, nnz, TBE_SUM, lr, eps, momentum_scale,
+                         tables, state, workspace, workspace_bytes, hip_stream, 1, grad_elems);
 }
 
 tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,

@@ -62,7 +62,9 @@ struct SegArgs {
     const uint32_t* counters;     // [0]=U, [1]=n_long, [2]=n_chunks
     const uint32_t* bag_sorted;   // linear bag id of every sorted position
     IdxView offsets;
-    const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT
+    const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT (or the sequence layout)
+    const int64_t* seq_gbase;     // non-pooled mode only: element offset of table t's gradient block minus start_t * D_t
+    int seq;                      // 1: non-pooled; bag_sorted then holds the original positions
     const int32_t* D_off;
     const int64_t* row_base;
     const int64_t* w_off;
@@ -89,6 +91,21 @@ __device__ __forceinline__ float bag_scale(const IdxView offsets, uint32_t bag) 
     return L > 0 ? 1.f / (float)L : 0.f;
 }
 
+// Where the upstream gradient of a lookup of table t lives: element base + (row - row0) * pitch (+ column).
+// Pooled: row = bag id, one [B, sum(D)] matrix.  Non-pooled: row = original position, one [n_t, D_t] block per table.
+struct GradAddr {
+    int64_t base, pitch, row0;
+};
+__device__ __forceinline__ GradAddr grad_addr(const SegArgs& a, const int t, const int D) {
+    GradAddr ga;
+    if (a.seq) {
+        ga.base = a.seq_gbase[t]; ga.pitch = D; ga.row0 = 0;
+    } else {
+        ga.base = a.D_off[t]; ga.pitch = a.sumD; ga.row0 = (int64_t)t * a.B;
+    }
+    return ga;
+}
+
 // Whole-wavefront reduction of sorted positions [s, e) of ONE row:
 // acc += sum of scale(bag) * grad_out[b, d0 + col .. col+3]; the groups take interleaved positions and
 // fold_groups() completes the sum.  NC = 256-column chunks per row.
@@ -100,11 +117,11 @@ __device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeo
     const int lane = lane_id();
     for (uint32_t base = s; base < e; base += kWave) {
         const int n = (int)((e - base) < (uint32_t)kWave ? (e - base) : (uint32_t)kWave);
-        int32_t my_b = 0;
+        uint32_t my_b = 0;
         float my_s = 1.f;
         if (lane < n) {
             const uint32_t bag = bag_sorted[base + lane];
-            my_b = (int32_t)((int64_t)bag - bag0);
+            my_b = (uint32_t)((int64_t)bag - bag0);
             my_s = bag_scale<MEAN>(offsets, bag);
         }
         for (int k0 = 0; k0 < n; k0 += kSegUnroll * g.G) {
@@ -113,7 +130,7 @@ __device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeo
 #pragma unroll
             for (int u = 0; u < kSegUnroll; ++u) {
                 const int k = k0 + u * g.G + g.sub;
-                const int32_t b = __shfl(my_b, k & (kWave - 1), kWave);
+                const uint32_t b = __shfl(my_b, k & (kWave - 1), kWave);
                 sc[u] = MEAN ? __shfl(my_s, k & (kWave - 1), kWave) : 1.f;
                 const bool on = k < n;
 #pragma unroll
@@ -203,6 +220,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
 // A hot row thus has 8 partial sums, one per XCD, accumulated over the sweeps.
 // Hot rows of tables whose gradient block fits the L2 anyway are cut into up to 16 equal parts instead.
 constexpr int kMaxParts = 16;
+constexpr int kMaxPartsSeq = 1024;
 constexpr uint32_t kSliceBytes = (uint32_t)TBE_SLICE_KB << 10;
 
 constexpr uint32_t kSlicedFlag = 0x80000000u;
@@ -244,7 +262,7 @@ struct LongPlan {
     uint32_t C;       // units per (XCD, sweep) if sliced, else number of equal shares
     uint32_t nslots;  // partial sums of the row
 };
-__device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t len) {
+__device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t len, bool seq) {
     LongPlan p;
     const uint32_t S = slices_for(B, D);
     if (S >= 8u) {
@@ -256,7 +274,9 @@ __device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t l
         p.sliced = false;
         p.nsub = 1;
         p.C = (len + kSegChunk - 1) / kSegChunk;
-        if (p.C > (uint32_t)kMaxParts) p.C = kMaxParts;
+        // non-pooled: every lookup has a gradient row of its own, nothing to keep in a cache, so just more parts
+        const uint32_t cap = seq ? (uint32_t)kMaxPartsSeq : (uint32_t)kMaxParts;
+        if (p.C > cap) p.C = cap;
         p.nslots = p.C;
     }
     return p;
@@ -283,7 +303,7 @@ __global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, uin
         const uint32_t u = rl.x;
         const int t = (int)rl.y;
         const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
-        const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len);
+        const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len, a.seq != 0);
         const uint32_t pos = tbase[t] + atomicAdd(&tfill[t], 1u);
         const uint32_t slot = atomicAdd(&counters[2], p.nslots);
         if (pos >= a.cap_long) continue;  // never true: at most n/(kSegChunk+1) rows are long
@@ -410,7 +430,8 @@ __device__ __forceinline__ void long_unit(const SegArgs& a, const uint32_t sweep
     float acc[NC][4];
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) acc[cc][0] = acc[cc][1] = acc[cc][2] = acc[cc][3] = 0.f;
-    segment_reduce<NC, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + d0, a.sumD, (int64_t)t * a.B,
+    const GradAddr ga = grad_addr(a, t, g.D);
+    segment_reduce<NC, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0,
                                  a.bag_sorted, a.offsets, lo, hi);
     fold_groups<NC>(acc, g);
     if (g.sub == 0) {
@@ -505,9 +526,9 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                 const int t_r = __shfl(t, r, kWave);
                 const float v_r = __shfl(v, r, kWave);
                 float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
-                segment_reduce<1, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + a.D_off[t_r], a.sumD,
-                                            (int64_t)t_r * a.B, a.bag_sorted,
-                                        a.offsets, s_r, s_r + len_r);
+                const GradAddr ga = grad_addr(a, t_r, g.D);
+                segment_reduce<1, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0,
+                                            a.bag_sorted, a.offsets, s_r, s_r + len_r);
                 fold_groups<1>(acc, g);
                 WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
                 adagrad_row<WT, 1>(acc, g, wrow, a.state + key_r, v_r, g.sub == 0, a.lr, a.eps, a.inv_c, a.state == nullptr);
@@ -537,8 +558,9 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             const float gv = __shfl(v, gi, kWave);
             const int goff = (int)(gs - s_r);
             const bool col_on = g.lc < g.D;
-            const GT* gcol = static_cast<const GT*>(a.grad_out) + a.D_off[gt] + g.lc;
-            const int64_t bag0 = (int64_t)gt * a.B;
+            const GradAddr ga = grad_addr(a, gt, g.D);
+            const GT* gcol = static_cast<const GT*>(a.grad_out) + ga.base + g.lc;
+            const int64_t bag0 = ga.row0;
             WT* wrow = tables + a.w_off[gt] + ((int64_t)gkey - a.row_base[gt]) * g.D;
             uint32_t lmax = glen;  // longest row of the round (wave-uniform loop bound)
             for (int o = g.LPR; o < kWave; o <<= 1) {
@@ -556,7 +578,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                     const uint32_t bag = __shfl(my_bag, src, kWave);
                     sc[uu] = MEAN ? __shfl(my_s, src, kWave) : 1.f;
                     const bool on = qi < glen && col_on;
-                    x[uu] = on ? GradIO<GT>::load(gcol + ((int64_t)bag - bag0) * a.sumD) : GradIO<GT>::zero();
+                    x[uu] = on ? GradIO<GT>::load(gcol + ((int64_t)bag - bag0) * ga.pitch) : GradIO<GT>::zero();
                 }
 #pragma unroll
                 for (int uu = 0; uu < kSegUnroll; ++uu) {
@@ -602,7 +624,8 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         float acc[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-        segment_reduce<4, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + d0, a.sumD, (int64_t)t * a.B, a.bag_sorted,
+        const GradAddr ga = grad_addr(a, t, g.D);
+        segment_reduce<4, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0, a.bag_sorted,
                                     a.offsets, s, e);
         fold_groups<4>(acc, g);
         adagrad_row<WT, 4>(acc, g, wrow, a.state + key, a.state ? a.state[key] : 0.f, g.sub == 0, a.lr, a.eps, a.inv_c,
@@ -707,14 +730,44 @@ static void launch_long_partial(const SegArgs& a, uint32_t sweep, bool mean, boo
     }
 }
 
+// non-pooled mode: element offset of every table's gradient block, minus start_t * D_t, so that the kernels address
+// a lookup by its original position alone
+// If offsets is not ascending from 0 to nnz, or the blocks do not fit grad_elems, no gradient address can be
+// trusted: the batch is then flagged as an index error and the number of unique rows set to zero, which turns the
+// update kernels that follow into no-ops.
+__global__ void seq_gbase_kernel(const IdxView offsets, const int32_t* __restrict__ D_off, const int T, const int64_t nnz,
+                                 const int64_t grad_elems, int64_t* __restrict__ gbase, uint32_t* __restrict__ counters,
+                                 int32_t* __restrict__ err) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int64_t acc = 0;
+    bool ok = offsets[0] == 0 && offsets[T] == nnz;
+    for (int t = 0; t < T; ++t) {
+        const int64_t s0 = offsets[t], s1 = offsets[t + 1];
+        const int64_t D = D_off[t + 1] - D_off[t];
+        ok = ok && s1 >= s0;
+        gbase[t] = acc - s0 * D;
+        acc += (s1 > s0 ? s1 - s0 : 0) * D;
+    }
+    if (!ok || acc > grad_elems) {
+        counters[0] = 0u;
+        atomicOr(err, 1);
+    }
+}
+
 hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,
                                  int grad_io, const void* offsets, int idx32, int32_t B, tbe_pooling pooling, float lr,
-                                 float eps, float c, void* tables, float* state, hipStream_t s) {
+                                 float eps, float c, void* tables, float* state, int seq, int64_t grad_elems, hipStream_t s) {
     SegArgs a;
+    a.seq = seq;
+    a.seq_gbase = reinterpret_cast<const int64_t*>(ws + w.seq_gbase);
+
     a.keys_unique = reinterpret_cast<const uint32_t*>(ws + w.vals[spare]);
     a.seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     a.counters = counters;
+    if (seq)
+        seq_gbase_kernel<<<1, 64, 0, s>>>(IdxView{offsets, idx32}, h->d_D_off, h->T, (int64_t)w.n, grad_elems,
+                                          reinterpret_cast<int64_t*>(ws + w.seq_gbase), counters, h->d_err);
     a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[spare]);
     a.offsets = IdxView{offsets, idx32};
     a.grad_out = grad_out;

@@ -153,4 +153,142 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     return hipGetLastError();
 }
 
+// ---- non-pooled lookup -------------------------------------------------------------------------------------
+// out block of table t = [n_t, D_t], row i = W_t[indices[offsets[t] + i]]; the blocks follow one another.
+// A wavefront takes 64 consecutive positions: every lane resolves one lookup (table, source row, destination),
+// then the 16-byte fragments of all 64 rows are copied lane-parallel, four in flight per lane.
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)(v & 0xFFFFFFFFll), o, kWave);
+        const uint32_t hi = __shfl_xor((uint32_t)((uint64_t)v >> 32), o, kWave);
+        v += (int64_t)(((uint64_t)hi << 32) | lo);
+    }
+    return v;
+}
+
+template <typename WT>
+__device__ __forceinline__ void copy_fragment(const WT* __restrict__ src, void* __restrict__ out, const int out_io,
+                                              const int64_t elem, const bool zero) {
+    constexpr int V = RowIO<WT>::kVec;
+    float x[V];
+    if (zero) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = 0.f;
+    } else {
+        RowIO<WT>::load(src, x);
+    }
+#pragma unroll
+    for (int v4 = 0; v4 < V; v4 += 4) store4_from_float(out, out_io, elem + v4, x[v4], x[v4 + 1], x[v4 + 2], x[v4 + 3]);
+}
+
+template <typename WT>
+__global__ __launch_bounds__(kFwdThreads, 8) void lookup_seq_kernel(
+    const WT* __restrict__ weights, const IdxView indices, const IdxView offsets, const int32_t* __restrict__ D_off,
+    const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base, const int T, const int64_t nnz,
+    void* __restrict__ out, const int out_io, const int64_t out_elems, int32_t* err) {
+    constexpr int V = RowIO<WT>::kVec;
+    const int lane = lane_id();
+    const int64_t p0 = ((int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6)) * kWave;
+    if (p0 >= nnz) return;
+    const int64_t p = p0 + lane;
+    const bool valid = p < nnz;
+    // table of the position: the last t with offsets[t] <= p (empty tables are skipped by construction)
+    int t = 0;
+    {
+        const int64_t q = valid ? p : p0;
+        int lo = 0, hi = T;  // invariant: offsets[lo] <= q, answer in [lo, hi)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (offsets[mid] <= q) lo = mid;
+            else hi = mid;
+        }
+        t = lo;
+    }
+    // element offset of the table's block: sum over earlier tables of n_t' * D_t'
+    const int t0 = __shfl(t, 0, kWave);
+    int64_t part = 0;
+    for (int tt = lane; tt < t0; tt += kWave) {
+        const int64_t n = offsets[tt + 1] - offsets[tt];
+        part += (n > 0 ? n : 0) * (int64_t)(D_off[tt + 1] - D_off[tt]);
+    }
+    int64_t base = wave_sum_i64(part);
+    for (int tt = t0; tt < t; ++tt) {
+        const int64_t n = offsets[tt + 1] - offsets[tt];
+        base += (n > 0 ? n : 0) * (int64_t)(D_off[tt + 1] - D_off[tt]);
+    }
+    const int D = D_off[t + 1] - D_off[t];
+    int64_t id = valid ? indices[p] : 0;
+    const int64_t R = row_base[t + 1] - row_base[t];
+    bool bad = false;
+    if (valid && (id < 0 || id >= R)) {
+        atomicOr(err, 1);   // as in the pooled forward: flagged, and the row reads as zeros
+        bad = true;
+        id = 0;
+    }
+    const int64_t src_elem = w_off[t] + id * D;
+    int64_t dst_elem = base + (p - offsets[t]) * D;
+    // a malformed offsets array (not ascending from 0 to nnz) must never take a store outside out[0, out_elems)
+    if (valid && (dst_elem < 0 || dst_elem + D > out_elems)) {
+        atomicOr(err, 1);
+        dst_elem = -1;
+    }
+    const int n = (int)((nnz - p0) < (int64_t)kWave ? (nnz - p0) : (int64_t)kWave);
+    const int F = D / V;  // fragments per row
+    const bool uniform = __all(!valid || D == __shfl(D, 0, kWave));
+    if (uniform) {
+        const int F0 = __shfl(F, 0, kWave);
+        const int total = n * F0;
+        for (int q0 = 0; q0 < total; q0 += 4 * kWave) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * kWave + lane;
+                const int k = q / F0, f = q - k * F0;
+                const int ks = k < n ? k : 0;
+                const uint32_t s_lo = __shfl((uint32_t)(src_elem & 0xFFFFFFFFll), ks, kWave);
+                const uint32_t s_hi = __shfl((uint32_t)((uint64_t)src_elem >> 32), ks, kWave);
+                const uint32_t d_lo = __shfl((uint32_t)(dst_elem & 0xFFFFFFFFll), ks, kWave);
+                const uint32_t d_hi = __shfl((uint32_t)((uint64_t)dst_elem >> 32), ks, kWave);
+                const int zb = __shfl((int)bad, ks, kWave);
+                const int64_t d0 = (int64_t)(((uint64_t)d_hi << 32) | d_lo);
+                if (q < total && d0 >= 0) {
+                    const int64_t se = (int64_t)(((uint64_t)s_hi << 32) | s_lo) + (int64_t)f * V;
+                    copy_fragment<WT>(weights + se, out, out_io, d0 + (int64_t)f * V, zb != 0);
+                }
+            }
+        }
+    } else {  // a table boundary inside the 64 positions: row by row
+        for (int k = 0; k < n; ++k) {
+            const uint32_t s_lo = __shfl((uint32_t)(src_elem & 0xFFFFFFFFll), k, kWave);
+            const uint32_t s_hi = __shfl((uint32_t)((uint64_t)src_elem >> 32), k, kWave);
+            const uint32_t d_lo = __shfl((uint32_t)(dst_elem & 0xFFFFFFFFll), k, kWave);
+            const uint32_t d_hi = __shfl((uint32_t)((uint64_t)dst_elem >> 32), k, kWave);
+            const int zb = __shfl((int)bad, k, kWave);
+            const int Fk = __shfl(F, k, kWave);
+            const int64_t d0 = (int64_t)(((uint64_t)d_hi << 32) | d_lo);
+            for (int f = lane; f < Fk && d0 >= 0; f += kWave) {
+                const int64_t se = (int64_t)(((uint64_t)s_hi << 32) | s_lo) + (int64_t)f * V;
+                copy_fragment<WT>(weights + se, out, out_io, d0 + (int64_t)f * V, zb != 0);
+            }
+        }
+    }
+}
+
+hipError_t launch_lookup_seq(const tbe_handle* h, const void* tables, const void* indices_p, const void* offsets_p,
+                             int idx32, int64_t nnz, void* out, int out_io, int64_t out_elems, hipStream_t s) {
+    if (nnz == 0) return hipSuccess;
+    const IdxView indices{indices_p, idx32}, offsets{offsets_p, idx32};
+    const int64_t per_block = (int64_t)(kFwdThreads / kWave) * kWave;
+    const dim3 grid((unsigned)((nnz + per_block - 1) / per_block));
+    LaunchTimer tm(h, s, "lookup_seq");
+    if (h->dtype == TBE_F32)
+        lookup_seq_kernel<float><<<grid, kFwdThreads, 0, s>>>(static_cast<const float*>(tables), indices, offsets, h->d_D_off,
+                                                              h->d_w_off, h->d_row_base, h->T, nnz, out, out_io, out_elems, h->d_err);
+    else
+        lookup_seq_kernel<__half><<<grid, kFwdThreads, 0, s>>>(static_cast<const __half*>(tables), indices, offsets,
+                                                               h->d_D_off, h->d_w_off, h->d_row_base, h->T, nnz, out, out_io,
+                                                               out_elems, h->d_err);
+    tm.done();
+    return hipGetLastError();
+}
+
 }  // namespace tbe

@@ -61,12 +61,13 @@ namespace tbe {
 struct Workspace {
     // keys/vals: radix double buffers of N+1 words each.  After the sort the buffer pair that does not hold the
     // result is reused: keys[spare] <- bag id of every sorted position, vals[spare] <- unique_rows.
-    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, raw_long,
+    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, raw_long,
         long_list, unit_list, bounds, partial, total;
     int radix_blocks;     // G
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;
     int64_t cap_long, cap_chunks, cap_units;
+    int64_t n;            // number of lookups the workspace was carved for
 };
 Workspace carve(const tbe_handle* h, int64_t N);
 
@@ -92,9 +93,17 @@ hipError_t launch_linearize(const tbe_handle* h, const void* indices, const void
 // (0/1) holds the sorted keys and positions
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
 // `sorted` is the buffer index (0/1) that holds the sorted (key, position) pairs; the other pair is overwritten
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);
+// seq != 0 (non-pooled mode): the per-position stream the gradient kernels read holds the original positions
+// instead of bag ids
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, int seq,
+                              hipStream_t s);
+// state == nullptr: plain SGD step.  seq != 0: grad_out is the non-pooled layout (one [n_t, D_t] block per table),
+// offsets has T+1 entries and B is 1.
 hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,
                                  int grad_io, const void* offsets, int idx32, int32_t B, tbe_pooling pooling, float lr,
-                                 float eps, float c, void* tables, float* state, hipStream_t s);
+                                 float eps, float c, void* tables, float* state, int seq, int64_t grad_elems, hipStream_t s);
+// non-pooled lookup: out block of table t = rows indices[offsets[t] .. offsets[t+1]) of table t, one after the other
+hipError_t launch_lookup_seq(const tbe_handle* h, const void* tables, const void* indices, const void* offsets, int idx32,
+                             int64_t nnz, void* out, int out_io, int64_t out_elems, hipStream_t s);
 
 }  // namespace tbe

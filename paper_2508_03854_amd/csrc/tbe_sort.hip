@@ -403,7 +403,8 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
             pv[k] = i < N ? vals[i] : 0u;
         }
 #pragma unroll
-        for (int k = 0; k < kRleItems; ++k) bg[k] = bag_of_pos[pv[k]];   // pv is a valid position (0 for the tail)
+        for (int k = 0; k < kRleItems; ++k)   // pv is a valid position (0 for the tail); non-pooled mode keeps it
+            bg[k] = bag_of_pos ? bag_of_pos[pv[k]] : pv[k];
 #pragma unroll
         for (int k = 0; k < kRleItems; ++k) {
             const int64_t i = base + k * kRleThreads + threadIdx.x;
@@ -434,10 +435,11 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
     }
 }
 
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s) {
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, int seq,
+                              hipStream_t s) {
     const uint32_t* keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[sorted]);
     const uint32_t* vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[sorted]);
-    const uint32_t* bag_of_pos = reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos);
+    const uint32_t* bag_of_pos = seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos);
     uint32_t* counts = reinterpret_cast<uint32_t*>(ws + w.rle_counts);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     uint32_t* bag_sorted = reinterpret_cast<uint32_t*>(ws + w.keys[sorted ^ 1]);

@@ -435,3 +435,73 @@ def test_sgd_matches_library_embedding_bag_with_sgd(oracle_mod, mode):
     mine = [W0.copy()]
     oracle_mod.backward_sgd(mine, go, idx, off, B, mode, lr=0.25)
     np.testing.assert_allclose(mine[0], emb.weight.detach().numpy(), rtol=1e-5, atol=1e-6)
+
+
+# ---- non-pooled lookup --------------------------------------------------------------------------------------
+def _seq_problem(rng, Rs=(9, 4, 6), Ds=(4, 8, 4), ns=(11, 0, 7), dtype=np.float32):
+    tables = [rng.standard_normal((R, D)).astype(dtype) for R, D in zip(Rs, Ds)]
+    toff = np.concatenate([[0], np.cumsum(ns)]).astype(np.int64)
+    idx = np.concatenate([rng.integers(0, R, size=n) for R, n in zip(Rs, ns)]).astype(np.int64)
+    return tables, idx, toff
+
+
+def test_lookup_seq_is_row_indexing(oracle_mod):
+    rng = np.random.default_rng(31)
+    tables, idx, toff = _seq_problem(rng)
+    out = oracle_mod.lookup_seq(tables, idx, toff)
+    want = np.concatenate([tables[t][idx[toff[t]:toff[t + 1]]].reshape(-1) for t in range(3)])   # the library's gather
+    assert np.array_equal(out.view(np.uint32), want.view(np.uint32))
+    # 16-bit output: each element rounded once
+    out16 = oracle_mod.lookup_seq(tables, idx, toff, out_dtype="f16")
+    assert np.array_equal(out16.view(np.uint16), want.astype(np.float16).view(np.uint16))
+    with pytest.raises(IndexError):
+        oracle_mod.lookup_seq(tables, np.where(np.arange(idx.size) == 3, 99, idx), toff)
+
+
+def test_backward_seq_equals_one_lookup_bags_and_dense_one_hot(oracle_mod):
+    rng = np.random.default_rng(32)
+    tables, idx, toff = _seq_problem(rng, Rs=(9,), Ds=(4,), ns=(25,))
+    n, D = 25, 4
+    g = rng.standard_normal((n, D)).astype(np.float32)
+    v0 = rng.uniform(0.0, 1.0, 9).astype(np.float32)
+    # (a) a sequence is the pooled layout with one lookup per bag: same rows, same bits
+    a_w, a_v = [tables[0].copy()], v0.copy()
+    U = oracle_mod.backward_seq(a_w, a_v, g.reshape(-1), idx, toff, lr=0.1, eps=1e-8, c=2.0)
+    b_w, b_v = [tables[0].copy()], v0.copy()
+    res = oracle_mod.backward_rowwise_adagrad(b_w, b_v, g, idx, np.arange(n + 1), n, "sum", 0.1, 1e-8, 2.0)
+    assert U == res.U == len(set(idx.tolist()))
+    assert np.array_equal(a_w[0].view(np.uint32), b_w[0].view(np.uint32)) and np.array_equal(a_v.view(np.uint32), b_v.view(np.uint32))
+    # (b) dense form: G = onehot^T . g, v += ||G_r||^2, w -= lr / (sqrt(v/c) + eps) * G_r
+    onehot = np.zeros((n, 9))
+    onehot[np.arange(n), idx] = 1.0
+    G = onehot.T @ g.astype(np.float64)
+    v = v0.astype(np.float64) + (G * G).sum(axis=1)
+    hit = onehot.sum(axis=0) > 0
+    want = tables[0].astype(np.float64) - (0.1 / (np.sqrt(v / 2.0) + 1e-8))[:, None] * G
+    np.testing.assert_allclose(a_w[0][hit], want[hit], rtol=1e-6)
+    np.testing.assert_allclose(a_v[hit], v[hit], rtol=1e-6)
+    assert np.array_equal(a_w[0][~hit].view(np.uint32), tables[0][~hit].view(np.uint32))
+    assert np.array_equal(a_v[~hit].view(np.uint32), v0[~hit].view(np.uint32))
+
+
+def test_backward_seq_several_tables_and_sgd(oracle_mod):
+    rng = np.random.default_rng(33)
+    tables, idx, toff = _seq_problem(rng)
+    Ds, ns = (4, 8, 4), (11, 0, 7)
+    total = sum(n * D for n, D in zip(ns, Ds))
+    g = rng.standard_normal(total).astype(np.float32)
+    new = [a.copy() for a in tables]
+    U = oracle_mod.backward_seq(new, None, g, idx, toff, lr=0.5)
+    base = 0
+    count = 0
+    for t in range(3):
+        n, D = ns[t], Ds[t]
+        gt = g[base:base + n * D].reshape(n, D).astype(np.float64)
+        ids = idx[toff[t]:toff[t + 1]]
+        want = tables[t].astype(np.float64)
+        np.subtract.at(want, ids, 0.5 * gt)           # the library's scatter-add, duplicates accumulate
+        np.testing.assert_allclose(new[t], want, rtol=1e-6, atol=1e-7)
+        count += len(set(ids.tolist()))
+        base += n * D
+    assert U == count
+    assert np.array_equal(new[1].view(np.uint32), tables[1].view(np.uint32))   # the empty table is untouched

@@ -355,6 +355,20 @@ def make_grad_out(cfg: Config, step: int = 0, device="cpu") -> torch.Tensor:
     return torch.randn(cfg.B, cfg.sum_D, generator=g, dtype=torch.float32, device=device)
 
 
+def as_sequence(cfg: Config, indices: torch.Tensor, offsets: torch.Tensor):
+    """The same ids read as a non-pooled (sequence) feature: table t owns positions offsets[t*B] .. offsets[(t+1)*B].
+    Returns (indices, table_offsets [T+1], number of output elements sum_t n_t * D_t)."""
+    toff = offsets[:: cfg.B].contiguous()
+    n_t = (toff[1:] - toff[:-1]).tolist()
+    return indices, toff, int(sum(n * d for n, d in zip(n_t, cfg.D)))
+
+
+def make_grad_seq(cfg: Config, total_elems: int, step: int = 0, device="cpu") -> torch.Tensor:
+    """Upstream gradient of a non-pooled lookup, N(0,1), float32, flat (one [n_t, D_t] block per table)."""
+    g = _gen(device, _stream_seed(cfg.seed, 107, step))
+    return torch.randn(max(1, total_elems), generator=g, dtype=torch.float32, device=device)[:total_elems]
+
+
 def describe(cfg: Config) -> str:
     return (f"{cfg.name}: T={cfg.T} rows={cfg.total_rows:,} sumD={cfg.sum_D} {cfg.weight_dtype} "
             f"weights={cfg.weight_bytes / 1e9:.2f}GB B={cfg.B} E[L]={cfg.expected_L():.1f} "
