@@ -152,9 +152,13 @@ tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, siz
 
 /* Parity hooks: DEVICE pointers into `workspace` holding the integer by-products of the last backward
  * call made with the same (h, workspace, B, nnz); valid until the next backward on that workspace.
- *   keys_sorted[nnz], vals_sorted[nnz] (original positions p, ascending inside a run of equal keys),
+ *   keys_sorted[nnz]  linearised row keys, ascending
+ *   vals_sorted[nnz]  what travelled with each key through the stable sort: after a pooled call the linear bag id
+ *                     t*B+b of the lookup (non-decreasing inside a run of equal keys, because positions are
+ *                     bag-major and the sort is stable); after a non-pooled call the original position p
+ *                     (ascending inside a run of equal keys)
  *   unique_rows[*num_unique] ascending, seg_start[*num_unique + 1] (seg_start[U] = nnz), num_unique[1].
- * Invalid ids, if any, appear as one trailing pseudo-row with key sum(rows). */
+ * Invalid ids, if any, appear as one trailing pseudo-row with key sum(rows).  Non-pooled calls: pass B = 1. */
 tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int64_t nnz,
                             const uint32_t** keys_sorted, const uint32_t** vals_sorted, const uint32_t** unique_rows,
                             const uint32_t** seg_start, const uint32_t** num_unique);

@@ -250,9 +250,10 @@ static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_i
                                     reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
     if (e != hipSuccess) return TBE_EHIP;
     int buf = 0;
-    e = launch_radix_sort(h, w, ws, nnz, &buf, s);
+    // pooled: the bag id of every position travels with its key; non-pooled: the position itself
+    e = launch_radix_sort(h, w, ws, nnz, seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos), &buf, s);
     if (e != hipSuccess) return TBE_EHIP;
-    e = launch_run_lengths(h, w, ws, buf, nnz, seq, s);
+    e = launch_run_lengths(h, w, ws, buf, nnz, s);
     if (e != hipSuccess) return TBE_EHIP;
     e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, (int)grad_dtype, offsets, idx32, B, pooling, lr, eps,
                               momentum_scale, tables, state, seq, grad_elems, s);

@@ -768,7 +768,7 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     if (seq)
         seq_gbase_kernel<<<1, 64, 0, s>>>(IdxView{offsets, idx32}, h->d_D_off, h->T, (int64_t)w.n, grad_elems,
                                           reinterpret_cast<int64_t*>(ws + w.seq_gbase), counters, h->d_err);
-    a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[spare]);
+    a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[spare ^ 1]);   // the sorted payload stream
     a.offsets = IdxView{offsets, idx32};
     a.grad_out = grad_out;
     a.D_off = h->d_D_off;

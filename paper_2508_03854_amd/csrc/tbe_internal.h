@@ -59,8 +59,9 @@ namespace tbe {
 
 // Workspace carving for a batch of N lookups (all offsets in bytes, 256-byte aligned).
 struct Workspace {
-    // keys/vals: radix double buffers of N+1 words each.  After the sort the buffer pair that does not hold the
-    // result is reused: keys[spare] <- bag id of every sorted position, vals[spare] <- unique_rows.
+    // keys/vals: radix double buffers of N+1 words each.  The payload of a key is the linear bag id of its lookup
+    // (pooled calls) or its position (non-pooled calls), so vals[sorted] is the per-lookup stream the gradient
+    // kernels read.  After the sort vals[spare] receives unique_rows.
     size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, raw_long,
         long_list, unit_list, bounds, partial, total;
     int radix_blocks;     // G
@@ -89,14 +90,12 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
 hipError_t launch_replica_mean(const tbe_handle* h, void* const* replicas, int M, size_t count, bool f32, hipStream_t s);
 hipError_t launch_linearize(const tbe_handle* h, const void* indices, const void* offsets, int idx32, int32_t B, int64_t N,
                             uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s);
-// sorts keys[0] of the workspace with the positions 0..N-1 as payload; returns in *result_buf which buffer pair
-// (0/1) holds the sorted keys and positions
-hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf, hipStream_t s);
-// `sorted` is the buffer index (0/1) that holds the sorted (key, position) pairs; the other pair is overwritten
-// seq != 0 (non-pooled mode): the per-position stream the gradient kernels read holds the original positions
-// instead of bag ids
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, int seq,
-                              hipStream_t s);
+// sorts keys[0] of the workspace; the payload that travels with a key is payload[p] (nullptr: its position p);
+// returns in *result_buf which buffer pair (0/1) holds the sorted keys and payloads
+hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, const uint32_t* payload,
+                             int* result_buf, hipStream_t s);
+// `sorted` is the buffer index (0/1) that holds the sorted pairs; vals of the other pair receive unique_rows
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);
 // state == nullptr: plain SGD step.  seq != 0: grad_out is the non-pooled layout (one [n_t, D_t] block per table),
 // offsets has T+1 entries and B is 1.
 hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,

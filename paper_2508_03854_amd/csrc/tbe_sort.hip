@@ -284,8 +284,8 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
     }
 }
 
-hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, int* result_buf,
-                             hipStream_t s) {
+hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, const uint32_t* payload,
+                             int* result_buf, hipStream_t s) {
     const int passes = (h->key_bits + 7) / 8;
     const int bits = (h->key_bits + passes - 1) / passes;  // <= 8
     const int nbins = 1 << bits;
@@ -296,7 +296,7 @@ hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, 
     int cur = 0;
     for (int p = 0; p < passes; ++p) {
         const uint32_t* kin = reinterpret_cast<const uint32_t*>(ws + w.keys[cur]);
-        const uint32_t* vin = reinterpret_cast<const uint32_t*>(ws + w.vals[cur]);
+        const uint32_t* vin = (p == 0 && payload) ? payload : reinterpret_cast<const uint32_t*>(ws + w.vals[cur]);
         uint32_t* kout = reinterpret_cast<uint32_t*>(ws + w.keys[cur ^ 1]);
         uint32_t* vout = reinterpret_cast<uint32_t*>(ws + w.vals[cur ^ 1]);
         const int shift = p * bits;
@@ -313,7 +313,7 @@ hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, 
         {
             LaunchTimer tm(h, s, "radix_scatter");
             radix_scatter_kernel<<<G, kRsThreads, 0, s>>>(kin, vin, kout, vout, N, w.radix_chunk, shift, mask, nbins, G,
-                                                          ghist, bin_tot, p == 0);
+                                                          ghist, bin_tot, p == 0 && !payload);
             tm.done();
         }
         cur ^= 1;
@@ -374,43 +374,20 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
     }
 }
 
-// Also resolves, for every sorted position, the bag that owns it (bag_sorted[i] = bag_of_pos[vals[i]]), so that
-// the gradient kernels read bag ids with coalesced loads instead of chasing two dependent gathers per lookup.
-__global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys,
-                                                                const uint32_t* __restrict__ vals,
-                                                                const uint32_t* __restrict__ bag_of_pos, const int64_t N,
+// Writes unique_rows and seg_start: element i is a head if its key differs from its predecessor's.
+__global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* __restrict__ keys, const int64_t N,
                                                                 const int ntiles,
                                                                 const uint32_t* __restrict__ block_base,
                                                                 uint32_t* __restrict__ unique_rows,
-                                                                uint32_t* __restrict__ seg_start,
-                                                                uint32_t* __restrict__ bag_sorted) {
+                                                                uint32_t* __restrict__ seg_start) {
     __shared__ uint32_t s_run[kRleRuns];
     const int lane = lane_id();
     const int w = threadIdx.x >> 6;
     const uint64_t lt = lanemask_lt();
-    // XCD-aware tile order: workgroup w runs on XCD w % 8; giving every XCD one contiguous eighth of the sorted
-    // sequence keeps the positions it resolves inside one or two tables, i.e. a bag_of_pos window that its L2 holds.
-    const uint32_t per_xcd = (gridDim.x + 7u) / 8u;
-    const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const uint32_t tile = blockIdx.x;
     if (tile >= (uint32_t)ntiles) return;
     const int64_t base = (int64_t)tile * kRleTile;
     uint64_t heads[kRleItems];
-    {   // all positions first, then all dependent gathers, then the stores: 8 independent chains in flight
-        uint32_t pv[kRleItems], bg[kRleItems];
-#pragma unroll
-        for (int k = 0; k < kRleItems; ++k) {
-            const int64_t i = base + k * kRleThreads + threadIdx.x;
-            pv[k] = i < N ? vals[i] : 0u;
-        }
-#pragma unroll
-        for (int k = 0; k < kRleItems; ++k)   // pv is a valid position (0 for the tail); non-pooled mode keeps it
-            bg[k] = bag_of_pos ? bag_of_pos[pv[k]] : pv[k];
-#pragma unroll
-        for (int k = 0; k < kRleItems; ++k) {
-            const int64_t i = base + k * kRleThreads + threadIdx.x;
-            if (i < N) bag_sorted[i] = bg[k];
-        }
-    }
 #pragma unroll
     for (int k = 0; k < kRleItems; ++k) {
         heads[k] = __ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N));
@@ -435,14 +412,10 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
     }
 }
 
-hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, int seq,
-                              hipStream_t s) {
+hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s) {
     const uint32_t* keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[sorted]);
-    const uint32_t* vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[sorted]);
-    const uint32_t* bag_of_pos = seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos);
     uint32_t* counts = reinterpret_cast<uint32_t*>(ws + w.rle_counts);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
-    uint32_t* bag_sorted = reinterpret_cast<uint32_t*>(ws + w.keys[sorted ^ 1]);
     uint32_t* unique_rows = reinterpret_cast<uint32_t*>(ws + w.vals[sorted ^ 1]);
     uint32_t* seg_start = reinterpret_cast<uint32_t*>(ws + w.seg_start);
     {
@@ -459,9 +432,7 @@ hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws,
     }
     {
         LaunchTimer tm(h, s, "rle_write");
-        const int grid = (w.rle_blocks + 7) / 8 * 8;  // whole rounds over the 8 XCDs
-        rle_write_kernel<<<grid, kRleThreads, 0, s>>>(keys_sorted, vals_sorted, bag_of_pos, N, w.rle_blocks, counts,
-                                                      unique_rows, seg_start, bag_sorted);
+        rle_write_kernel<<<w.rle_blocks, kRleThreads, 0, s>>>(keys_sorted, N, w.rle_blocks, counts, unique_rows, seg_start);
         tm.done();
     }
     return hipGetLastError();

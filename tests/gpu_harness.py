@@ -133,7 +133,9 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
         dbg = tbe.debug_sorted(ws, B, nnz)
         assert dbg["num_unique"] == res.U, (dbg["num_unique"], res.U)
         assert np.array_equal(dbg["keys_sorted"].numpy(), res.keys_sorted), "keys_sorted differs"
-        assert np.array_equal(dbg["vals_sorted"].numpy(), res.order), "stable order differs"
+        # the payload of the sort is the bag of each lookup: the oracle's stable order, mapped position -> bag
+        bag_of_order = np.searchsorted(off_np, res.order, side="right") - 1
+        assert np.array_equal(dbg["vals_sorted"].numpy(), bag_of_order), "stable order differs"
         assert np.array_equal(dbg["unique_rows"].numpy(), res.unique_rows), "unique_rows differs"
         assert np.array_equal(dbg["seg_start"].numpy(), res.seg_start), "seg_start differs"
     report["U"] = res.U
