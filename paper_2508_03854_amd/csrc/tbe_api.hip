@@ -33,8 +33,13 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     int64_t tiles_per_block = (tiles + G - 1) / G;
     w.radix_chunk = tiles_per_block * kRadixTile;
     w.radix_blocks = (int)(((int64_t)n + w.radix_chunk - 1) / w.radix_chunk);
-    w.radix_hist = take(4 * (size_t)256 * (size_t)w.radix_blocks);
-    w.bin_tot = take(4 * 256);
+    w.nseg = h->segmented ? h->T : 1;
+    w.radix_maxc = w.radix_blocks + w.nseg;
+    w.radix_hist = take(4 * (size_t)256 * (size_t)(w.radix_maxc + 1));
+    w.bin_tot = take(4 * 256 * (size_t)w.nseg);
+    w.seg_bounds = take(4 * (size_t)(w.nseg + 1));
+    w.seg_chunk0 = take(4 * (size_t)(w.nseg + 1));
+    w.chunk_desc = take(16 * (size_t)w.radix_maxc);
     w.rle_blocks = (int)(((int64_t)n + kRleTile - 1) / kRleTile);
     w.rle_counts = take(4 * (size_t)(w.rle_blocks + 1));
     w.counters = take(4 * kCounterWords);
@@ -140,6 +145,14 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     h->total_elems = h->w_off[T];
     h->sumD = (int32_t)sumD;
     h->key_bits = bits_for((uint64_t)h->total_rows);
+    {
+        int64_t max_rows = 0;
+        for (int t = 0; t < T; ++t) max_rows = rows[t] > max_rows ? rows[t] : max_rows;
+        const int local_bits = bits_for((uint64_t)max_rows);  // the local key of an invalid id is rows[t] itself
+        h->segmented = T > 1 && T <= kMaxSortSegments && (local_bits + 7) / 8 < (h->key_bits + 7) / 8;
+        h->sort_bits = h->segmented ? local_bits : h->key_bits;
+        h->sort_passes = (h->sort_bits + 7) / 8;
+    }
     if (hipGetDevice(&h->device) != hipSuccess) {
         delete h;
         return TBE_EHIP;
@@ -251,7 +264,8 @@ static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_i
     if (e != hipSuccess) return TBE_EHIP;
     int buf = 0;
     // pooled: the bag id of every position travels with its key; non-pooled: the position itself
-    e = launch_radix_sort(h, w, ws, nnz, seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos), &buf, s);
+    e = launch_radix_sort(h, w, ws, nnz, seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos), offsets,
+                          idx32, B, &buf, s);
     if (e != hipSuccess) return TBE_EHIP;
     e = launch_run_lengths(h, w, ws, buf, nnz, s);
     if (e != hipSuccess) return TBE_EHIP;
@@ -316,8 +330,7 @@ tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int
     const tbe_status st = check_batch(h, B, nnz);
     if (st != TBE_OK) return st;
     const Workspace w = carve(h, nnz);
-    const int passes = (h->key_bits + 7) / 8;
-    const int buf = passes & 1;  // every pass flips the double buffer, starting from 0
+    const int buf = h->sort_passes & 1;  // every pass flips the double buffer, starting from 0
     char* ws = static_cast<char*>(workspace);
     if (keys_sorted) *keys_sorted = reinterpret_cast<const uint32_t*>(ws + w.keys[buf]);
     if (vals_sorted) *vals_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[buf]);

@@ -16,10 +16,14 @@ constexpr int kSegChunk = 512;         // a unique row with more lookups than th
 #define TBE_RADIX_TILE 4096
 #endif
 constexpr int kRadixTile = TBE_RADIX_TILE;  // elements per radix-sort tile (256 threads x items per thread)
-constexpr int kRadixMaxBlocks = 2048;  // each radix block owns one contiguous slice of the input
+#ifndef TBE_RADIX_MAX_BLOCKS
+#define TBE_RADIX_MAX_BLOCKS 8192
+#endif
+constexpr int kRadixMaxBlocks = TBE_RADIX_MAX_BLOCKS;  // each radix block owns one contiguous slice of the input
 constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
+constexpr int kMaxSortSegments = 4096;  // tables beyond this are sorted as one segment on the linearised key
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
@@ -41,6 +45,12 @@ struct tbe_handle {
     int32_t sumD = 0;
     int32_t maxD = 0;
     int key_bits = 1;  // bits needed to hold the value total_rows (the key given to invalid ids)
+    // Sort plan.  Positions arrive grouped by table, so sorting every table's run of positions on its table-local id
+    // alone gives the same order as sorting all of them on the linearised key, with fewer key bits whenever
+    // bits(max rows of one table) needs fewer radix passes than bits(sum of rows).
+    bool segmented = false;  // true: one sort segment per table, local keys; false: one segment, linearised keys
+    int sort_bits = 1;       // key bits the radix passes cover
+    int sort_passes = 1;
     std::vector<int64_t> rows, row_base, w_off;
     std::vector<int32_t> D, D_off;
     // device metadata, one allocation
@@ -62,9 +72,12 @@ struct Workspace {
     // keys/vals: radix double buffers of N+1 words each.  The payload of a key is the linear bag id of its lookup
     // (pooled calls) or its position (non-pooled calls), so vals[sorted] is the per-lookup stream the gradient
     // kernels read.  After the sort vals[spare] receives unique_rows.
-    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, raw_long,
+    size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, seg_bounds,
+        seg_chunk0, chunk_desc, raw_long,
         long_list, unit_list, bounds, partial, total;
-    int radix_blocks;     // G
+    int radix_blocks;     // blocks a single segment of N keys would need
+    int radix_maxc;       // chunk descriptors: radix_blocks + number of segments (every segment may end in a partial chunk)
+    int nseg;             // sort segments
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;
     int64_t cap_long, cap_chunks, cap_units;
@@ -90,10 +103,11 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
 hipError_t launch_replica_mean(const tbe_handle* h, void* const* replicas, int M, size_t count, bool f32, hipStream_t s);
 hipError_t launch_linearize(const tbe_handle* h, const void* indices, const void* offsets, int idx32, int32_t B, int64_t N,
                             uint32_t* keys, uint32_t* bag_of_pos, hipStream_t s);
-// sorts keys[0] of the workspace; the payload that travels with a key is payload[p] (nullptr: its position p);
-// returns in *result_buf which buffer pair (0/1) holds the sorted keys and payloads
+// sorts keys[0] of the workspace segment by segment (see tbe_handle::segmented); the payload that travels with a key
+// is payload[p] (nullptr: its position p).  The keys written by the last pass are linearised row keys in either
+// mode.  Returns in *result_buf which buffer pair (0/1) holds the sorted keys and payloads.
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, const uint32_t* payload,
-                             int* result_buf, hipStream_t s);
+                             const void* offsets, int idx32, int32_t B, int* result_buf, hipStream_t s);
 // `sorted` is the buffer index (0/1) that holds the sorted pairs; vals of the other pair receive unique_rows
 hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws, int sorted, int64_t N, hipStream_t s);
 // state == nullptr: plain SGD step.  seq != 0: grad_out is the non-pooled layout (one [n_t, D_t] block per table),

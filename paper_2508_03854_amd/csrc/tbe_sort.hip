@@ -27,8 +27,8 @@ __device__ __forceinline__ int64_t upper_bound_i64(const IdxView a, int64_t lo, 
 __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView indices, const IdxView offsets,
                                                                 const int64_t nbags, const int32_t B,
                                                                 const int64_t* __restrict__ row_base,
-                                                                const uint32_t invalid_key, const int64_t N,
-                                                                uint32_t* __restrict__ keys,
+                                                                const uint32_t invalid_key, const bool local_keys,
+                                                                const int64_t N, uint32_t* __restrict__ keys,
                                                                 uint32_t* __restrict__ bag_of_pos, int32_t* err) {
     __shared__ int32_t s_off[kLinTile + 2];
     __shared__ int64_t s_lo, s_hi;
@@ -76,11 +76,13 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
         const int64_t rb = row_base[t];
         const int64_t R = row_base[t + 1] - rb;
         const int64_t id = indices[p];
+        // local_keys: the table-local id (an invalid id gets R, one past the table's last row); the sort's last
+        // pass turns it into the linearised key
         uint32_t key;
         if (id >= 0 && id < R) {
-            key = (uint32_t)(rb + id);
+            key = local_keys ? (uint32_t)id : (uint32_t)(rb + id);
         } else {
-            key = invalid_key;
+            key = local_keys ? (uint32_t)R : invalid_key;
             atomicOr(err, 1);
         }
         keys[p] = key;                  // the payload of position p is p itself: the first sort pass generates it
@@ -94,23 +96,79 @@ hipError_t launch_linearize(const tbe_handle* h, const void* indices_p, const vo
     const int64_t nbags = (int64_t)h->T * B;
     const unsigned grid = (unsigned)((N + kLinTile - 1) / kLinTile);
     LaunchTimer tm(h, s, "linearize");
-    linearize_kernel<<<grid, kLinThreads, 0, s>>>(indices, offsets, nbags, B, h->d_row_base, (uint32_t)h->total_rows, N,
-                                                  keys, bag_of_pos, h->d_err);
+    linearize_kernel<<<grid, kLinThreads, 0, s>>>(indices, offsets, nbags, B, h->d_row_base, (uint32_t)h->total_rows,
+                                                  h->segmented, N, keys, bag_of_pos, h->d_err);
     tm.done();
     return hipGetLastError();
 }
 
 // =================================================================================================
-// LSD radix sort, <= 8 bits per pass, 3 kernels per pass:
-//   hist    : block k counts the digits of its contiguous slice          -> ghist[digit][k]
-//   binscan : block d turns ghist[d][*] into an exclusive scan in place   -> bin_tot[d]
-//   scatter : block k ranks its slice tile by tile and writes (key, val) to its final place
-// Block k's slice precedes block k+1's, and the scatter ranks elements in input order, so the sort is stable.
+// Segmented LSD radix sort, <= 8 bits per pass.  The positions are cut into segments (one per table, or a single
+// one) and every segment into chunks of at most `chunk` positions; a chunk never crosses a segment border.
+//   plan    : segment borders from offsets, chunk descriptors (once per sort)
+//   hist    : block k counts the digits of chunk k                                   -> ghist[digit][k]
+//   binscan : block d turns ghist[d][*] into an exclusive scan per segment, in place -> bin_tot[segment][d]
+//   scatter : block k ranks its chunk tile by tile and writes (key, val) to its final place inside the segment
+// Chunk k precedes chunk k+1, and the scatter ranks elements in input order, so the sort is stable.
+// The last pass turns table-local keys into linearised ones as it writes them.
 // =================================================================================================
 constexpr int kRsThreads = 256;
 constexpr int kRsWaves = kRsThreads / kWave;
 constexpr int kRsItems = kRadixTile / kRsThreads;  // 8
 constexpr int kRsBins = 256;
+
+struct SortPlan {
+    const uint32_t* bounds;   // [nseg + 1] first position of every segment; bounds[nseg] = N
+    const uint32_t* chunk0;   // [nseg + 1] first chunk of every segment; chunk0[nseg] = number of chunks
+    const uint4* desc;        // [chunks] (first position, end position, segment, -)
+    int nseg;
+    int G;                    // row length of ghist (> number of chunks)
+};
+
+// One workgroup.  Segment borders: offsets[t * B], forced into [0, N] and made ascending, so that the chunks
+// always tile [0, N) exactly, whatever the offsets array holds.
+__global__ __launch_bounds__(1024) void radix_plan_kernel(const IdxView offsets, const int32_t B, const int nseg,
+                                                          const int64_t N, const int64_t chunk,
+                                                          uint32_t* __restrict__ bounds, uint32_t* __restrict__ chunk0,
+                                                          uint4* __restrict__ desc, const int maxc) {
+    __shared__ uint32_t s_b[kMaxSortSegments + 1];
+    __shared__ uint32_t s_c[kMaxSortSegments + 1];
+    for (int t = threadIdx.x; t <= nseg; t += 1024) {
+        int64_t b = (t == 0) ? 0 : (t == nseg ? N : offsets[(int64_t)t * B]);
+        b = b < 0 ? 0 : (b > N ? N : b);
+        s_b[t] = (uint32_t)b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {   // running maximum (ascending borders) and chunk counts; nseg is small
+        uint32_t run = 0, c = 0;
+        for (int t = 0; t <= nseg; ++t) {
+            const uint32_t b = s_b[t] > run ? s_b[t] : run;
+            if (t > 0) c += (uint32_t)(((int64_t)b - run + chunk - 1) / chunk);
+            run = b;
+            s_b[t] = b;
+            s_c[t] = c;   // chunks of the segments before t
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t <= nseg; t += 1024) {
+        bounds[t] = s_b[t];
+        chunk0[t] = s_c[t];
+    }
+    // chunk c belongs to the last segment t with chunk0[t] <= c (segments without chunks are skipped by this rule)
+    const uint32_t total = s_c[nseg] < (uint32_t)maxc ? s_c[nseg] : (uint32_t)maxc;
+    for (uint32_t c = threadIdx.x; c < total; c += 1024) {
+        int lo = 0, hi = nseg;   // invariant: s_c[lo] <= c, answer in [lo, hi)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_c[mid] <= c) lo = mid;
+            else hi = mid;
+        }
+        const int64_t s = (int64_t)s_b[lo] + (int64_t)(c - s_c[lo]) * chunk;
+        const int64_t s1 = s_b[lo + 1];
+        const int64_t e = s + chunk < s1 ? s + chunk : s1;
+        desc[c] = make_uint4((uint32_t)s, (uint32_t)e, (uint32_t)lo, 0u);
+    }
+}
 
 // One digit count into the wavefront's private histogram.  When every active lane holds the same digit (the
 // common case for the high digits, because ids arrive grouped by table) one lane adds the whole count instead of
@@ -127,18 +185,32 @@ __device__ __forceinline__ void hist_add(uint32_t* __restrict__ hw, const uint32
     }
 }
 
-__global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* __restrict__ keys, const int64_t N,
-                                                                const int64_t chunk, const int shift,
-                                                                const uint32_t mask, const int nbins, const int G,
+__global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* __restrict__ keys, const SortPlan pl,
+                                                                const int shift, const uint32_t mask, const int nbins,
                                                                 uint32_t* __restrict__ ghist) {
     __shared__ uint32_t h[kRsWaves][kRsBins];
+    const uint32_t nchunks = pl.chunk0[pl.nseg];
+    if (blockIdx.x >= nchunks) {   // unused column: zeros, so that the scan can run over the whole row
+        for (int d = threadIdx.x; d < nbins; d += kRsThreads) ghist[(size_t)d * pl.G + blockIdx.x] = 0u;
+        return;
+    }
     for (int i = threadIdx.x; i < kRsWaves * kRsBins; i += kRsThreads) (&h[0][0])[i] = 0u;
     __syncthreads();
     uint32_t* hw = h[threadIdx.x >> 6];
-    const int64_t s = (int64_t)blockIdx.x * chunk;  // multiple of 2048 elements: 16-byte aligned
-    const int64_t e = (s + chunk < N) ? s + chunk : N;
-    const int64_t n4 = e > s ? (e - s) >> 2 : 0;    // whole uint4 groups
-    const uint4* k4 = reinterpret_cast<const uint4*>(keys + s);
+    const uint4 ds = pl.desc[blockIdx.x];
+    const int64_t s = ds.x, e = ds.y;
+    // leading elements up to the next 16-byte boundary, whole uint4 groups, then up to 3 trailing elements
+    int64_t lead = (4 - (s & 3)) & 3;
+    if (lead > e - s) lead = e - s;
+    {
+        const int64_t i = s + threadIdx.x;
+        const bool valid = (int64_t)threadIdx.x < lead;
+        const uint32_t k = valid ? keys[i] : 0u;
+        hist_add(hw, (k >> shift) & mask, valid);
+    }
+    const int64_t s4 = s + lead;
+    const int64_t n4 = (e - s4) >> 2;
+    const uint4* k4 = reinterpret_cast<const uint4*>(keys + s4);
     for (int64_t base = 0; base < n4; base += kRsThreads) {
         const int64_t i = base + threadIdx.x;
         const bool valid = i < n4;
@@ -149,8 +221,8 @@ __global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* 
         hist_add(hw, (k.z >> shift) & mask, valid);
         hist_add(hw, (k.w >> shift) & mask, valid);
     }
-    {   // up to 3 trailing elements
-        const int64_t i = s + 4 * n4 + threadIdx.x;
+    {
+        const int64_t i = s4 + 4 * n4 + threadIdx.x;
         const bool valid = i < e;
         const uint32_t k = valid ? keys[i] : 0u;
         hist_add(hw, (k >> shift) & mask, valid);
@@ -160,36 +232,47 @@ __global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* 
         uint32_t c = 0;
 #pragma unroll
         for (int ww = 0; ww < kRsWaves; ++ww) c += h[ww][d];
-        ghist[(size_t)d * G + blockIdx.x] = c;
+        ghist[(size_t)d * pl.G + blockIdx.x] = c;
     }
 }
 
-// grid = nbins blocks; block d scans its G counts in place (exclusive) and writes the digit total
-__global__ __launch_bounds__(kRsThreads) void radix_binscan_kernel(uint32_t* __restrict__ ghist, const int G,
+// grid = nbins blocks; block d scans row d of ghist in place: first over all chunks, then every segment's part is
+// re-based to start at zero; bin_tot[segment][d] = number of keys with digit d in the segment
+__global__ __launch_bounds__(kRsThreads) void radix_binscan_kernel(uint32_t* __restrict__ ghist, const SortPlan pl,
                                                                    uint32_t* __restrict__ bin_tot) {
     __shared__ uint32_t smem[kRsWaves];
-    uint32_t* row = ghist + (size_t)blockIdx.x * G;
+    __shared__ uint32_t s_b0[kMaxSortSegments];
+    uint32_t* row = ghist + (size_t)blockIdx.x * pl.G;
+    const int nchunks = (int)pl.chunk0[pl.nseg];   // < G; row[nchunks] is an unused column holding zero
     uint32_t carry = 0;
-    for (int base = 0; base < G; base += kRsThreads) {
+    for (int base = 0; base <= nchunks; base += kRsThreads) {
         const int i = base + threadIdx.x;
-        const uint32_t v = (i < G) ? row[i] : 0u;
+        const uint32_t v = (i <= nchunks) ? row[i] : 0u;
         uint32_t tot;
         const uint32_t ex = block_excl_scan<kRsThreads>(v, smem, &tot);
-        if (i < G) row[i] = carry + ex;
+        if (i <= nchunks) row[i] = carry + ex;     // row[nchunks] = total
         carry += tot;
     }
-    if (threadIdx.x == 0) bin_tot[blockIdx.x] = carry;
+    __syncthreads();
+    for (int t = threadIdx.x; t < pl.nseg; t += kRsThreads) {
+        const uint32_t b0 = row[pl.chunk0[t]], b1 = row[pl.chunk0[t + 1]];
+        s_b0[t] = b0;
+        bin_tot[(size_t)t * kRsBins + blockIdx.x] = b1 - b0;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nchunks; i += kRsThreads) row[i] -= s_b0[pl.desc[i].z];
 }
 
 __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in,
                                                                    const uint32_t* __restrict__ vals_in,
                                                                    uint32_t* __restrict__ keys_out,
-                                                                   uint32_t* __restrict__ vals_out, const int64_t N,
-                                                                   const int64_t chunk, const int shift,
-                                                                   const uint32_t mask, const int nbins, const int G,
+                                                                   uint32_t* __restrict__ vals_out, const SortPlan pl,
+                                                                   const int shift, const uint32_t mask, const int nbins,
                                                                    const uint32_t* __restrict__ ghist,
                                                                    const uint32_t* __restrict__ bin_tot,
-                                                                   const bool iota_vals) {
+                                                                   const bool iota_vals, const int globalize,
+                                                                   const int64_t* __restrict__ row_base, const int32_t B,
+                                                                   const uint32_t invalid_key) {
     __shared__ uint32_t s_cnt[kRsWaves][kRsBins];  // per-wave digit counts, then per-wave exclusive offsets
     __shared__ uint32_t s_base[kRsBins];           // where this block's next element of digit d goes
     __shared__ uint32_t s_dstart[kRsBins];         // start of digit d inside the locally sorted tile
@@ -202,14 +285,17 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
     const int w = tid >> 6;
     const uint64_t lt = lanemask_lt();
 
-    {   // global base of every digit for this block: (digits below d, all blocks) + (digit d, blocks before this one)
-        const uint32_t t = (tid < nbins) ? bin_tot[tid] : 0u;
+    if (blockIdx.x >= pl.chunk0[pl.nseg]) return;
+    const uint4 ds = pl.desc[blockIdx.x];
+    const int64_t s = ds.x, e = ds.y;
+    const int seg = (int)ds.z;
+    {   // base of every digit for this chunk: segment start + (digits below d, whole segment) + (digit d, the
+        // segment's chunks before this one)
+        const uint32_t t = (tid < nbins) ? bin_tot[(size_t)seg * kRsBins + tid] : 0u;
         uint32_t tot;
         const uint32_t ex = block_excl_scan<kRsThreads>(t, s_scan, &tot);
-        s_base[tid] = (tid < nbins) ? ex + ghist[(size_t)tid * G + blockIdx.x] : 0u;
+        s_base[tid] = (tid < nbins) ? pl.bounds[seg] + ex + ghist[(size_t)tid * pl.G + blockIdx.x] : 0u;
     }
-    const int64_t s = (int64_t)blockIdx.x * chunk;
-    const int64_t e = (s + chunk < N) ? s + chunk : N;
 
     for (int64_t tile = s; tile < e; tile += kRadixTile) {
         for (int i = tid; i < kRsWaves * kRsBins; i += kRsThreads) (&s_cnt[0][0])[i] = 0u;
@@ -276,8 +362,17 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
             const uint32_t kk = s_keys[j];
             const uint32_t d = (kk >> shift) & mask;
             const uint32_t dst = s_base[d] + ((uint32_t)j - s_dstart[d]);
-            keys_out[dst] = kk;
-            vals_out[dst] = s_vals[j];
+            const uint32_t vv = s_vals[j];
+            uint32_t ko = kk;
+            if (globalize) {   // last pass of a segmented sort: table-local id -> linearised row key
+                // the table comes from the lookup's bag where the payload is one (so that key and bag always agree),
+                // else from the segment
+                const int t = globalize == 1 ? (int)(vv / (uint32_t)B) : seg;
+                const int64_t rb = row_base[t];
+                ko = ((int64_t)kk >= row_base[t + 1] - rb) ? invalid_key : (uint32_t)(rb + kk);
+            }
+            keys_out[dst] = ko;
+            vals_out[dst] = vv;
         }
         __syncthreads();
         s_base[tid] += my_tot;
@@ -285,14 +380,28 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
 }
 
 hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, int64_t N, const uint32_t* payload,
-                             int* result_buf, hipStream_t s) {
-    const int passes = (h->key_bits + 7) / 8;
-    const int bits = (h->key_bits + passes - 1) / passes;  // <= 8
+                             const void* offsets, int idx32, int32_t B, int* result_buf, hipStream_t s) {
+    const int passes = h->sort_passes;
+    const int bits = (h->sort_bits + passes - 1) / passes;  // <= 8
     const int nbins = 1 << bits;
     const uint32_t mask = (uint32_t)nbins - 1u;
-    const int G = w.radix_blocks;
     uint32_t* ghist = reinterpret_cast<uint32_t*>(ws + w.radix_hist);
     uint32_t* bin_tot = reinterpret_cast<uint32_t*>(ws + w.bin_tot);
+    SortPlan pl;
+    pl.bounds = reinterpret_cast<const uint32_t*>(ws + w.seg_bounds);
+    pl.chunk0 = reinterpret_cast<const uint32_t*>(ws + w.seg_chunk0);
+    pl.desc = reinterpret_cast<const uint4*>(ws + w.chunk_desc);
+    pl.nseg = w.nseg;
+    pl.G = w.radix_maxc + 1;
+    {
+        LaunchTimer tm(h, s, "radix_plan");
+        radix_plan_kernel<<<1, 1024, 0, s>>>(IdxView{offsets, idx32}, B, w.nseg, N, w.radix_chunk,
+                                             reinterpret_cast<uint32_t*>(ws + w.seg_bounds),
+                                             reinterpret_cast<uint32_t*>(ws + w.seg_chunk0),
+                                             reinterpret_cast<uint4*>(ws + w.chunk_desc), w.radix_maxc);
+        tm.done();
+    }
+    const int grid = w.radix_maxc;
     int cur = 0;
     for (int p = 0; p < passes; ++p) {
         const uint32_t* kin = reinterpret_cast<const uint32_t*>(ws + w.keys[cur]);
@@ -302,18 +411,21 @@ hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, 
         const int shift = p * bits;
         {
             LaunchTimer tm(h, s, "radix_hist");
-            radix_hist_kernel<<<G, kRsThreads, 0, s>>>(kin, N, w.radix_chunk, shift, mask, nbins, G, ghist);
+            radix_hist_kernel<<<grid + 1, kRsThreads, 0, s>>>(kin, pl, shift, mask, nbins, ghist);
             tm.done();
         }
         {
             LaunchTimer tm(h, s, "radix_binscan");
-            radix_binscan_kernel<<<nbins, kRsThreads, 0, s>>>(ghist, G, bin_tot);
+            radix_binscan_kernel<<<nbins, kRsThreads, 0, s>>>(ghist, pl, bin_tot);
             tm.done();
         }
         {
             LaunchTimer tm(h, s, "radix_scatter");
-            radix_scatter_kernel<<<G, kRsThreads, 0, s>>>(kin, vin, kout, vout, N, w.radix_chunk, shift, mask, nbins, G,
-                                                          ghist, bin_tot, p == 0 && !payload);
+            // the last pass of a segmented sort writes linearised keys: table from the bag id (pooled) or the segment
+            const int globalize = (h->segmented && p == passes - 1) ? (payload ? 1 : 2) : 0;
+            radix_scatter_kernel<<<grid, kRsThreads, 0, s>>>(kin, vin, kout, vout, pl, shift, mask, nbins, ghist, bin_tot,
+                                                             p == 0 && !payload, globalize, h->d_row_base, B,
+                                                             (uint32_t)h->total_rows);
             tm.done();
         }
         cur ^= 1;

@@ -315,3 +315,78 @@ def test_hand_worked_rows_of_algorithm_1_on_the_gpu():
             tbe.close()
         n += 1
     assert n == 5
+
+
+# ---- tables sorted segment by segment on their local ids (fewer key bits than the linearised key needs) ----------
+def test_segmented_sort_shapes(H):
+    # 3 x 250 rows: local ids need 8 bits (one radix pass), linearised keys 10 bits (two): the per-table path
+    rng = np.random.default_rng(7)
+    cfg = make_cfg([250, 250, 250], [8, 16, 8], B=700, pooling="sum", c=2.0)
+    lens = rng.integers(0, 6, size=3 * 700)
+    lens[700:1400] = 0                                    # the middle table sees no id at all
+    ids = np.concatenate([rng.integers(0, 250, size=int(lens[t * 700:(t + 1) * 700].sum())) for t in range(3)])
+    reps = run_custom(H, cfg, lens, ids, steps=2)
+    assert reps[0]["U"] > 300
+    # many small tables, some of them empty, ragged sizes that do not line up with any tile
+    T = 37
+    cfg = make_cfg([200 + 3 * t for t in range(T)], [8] * T, B=129, pooling="mean")
+    lens = rng.integers(0, 4, size=T * 129)
+    for t in (0, 5, 6, 36):
+        lens[t * 129:(t + 1) * 129] = 0
+    ids = np.concatenate([rng.integers(0, 200 + 3 * t, size=int(lens[t * 129:(t + 1) * 129].sum())) for t in range(T)])
+    run_custom(H, cfg, lens, ids)
+    # one table holds almost everything (many chunks), the others a handful of lookups
+    cfg = make_cfg([255, 255, 255, 255], [8, 8, 8, 8], B=50000, pooling="sum")
+    lens = np.zeros(4 * 50000, dtype=np.int64)
+    lens[50000:100000] = rng.integers(8, 12, size=50000)
+    lens[[3, 150001, 199999]] = 2
+    ids = np.concatenate([rng.integers(0, 255, size=int(lens[t * 50000:(t + 1) * 50000].sum())) for t in range(4)])
+    reps = run_custom(H, cfg, lens, ids)
+    assert reps[0]["max_seg"] > 1000
+
+
+def test_segmented_sort_invalid_ids_and_malformed_offsets():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    import oracle
+    rows, D, B = [250, 250, 250], [8, 8, 8], 4
+    tbe = TBE(rows, D, "f32")
+    g = torch.Generator().manual_seed(0)
+    flat_cpu = torch.randn(750 * 8, generator=g)
+    flat = flat_cpu.cuda()
+    lens = [2, 1, 0, 3, 1, 1, 2, 1, 0, 2, 2, 1]
+    good = torch.tensor([1, 249, 4, 0, 3, 3, 5, 0, 2, 1, 5, 7, 7, 100, 249, 3], dtype=torch.int64)
+    bad = good.clone()
+    bad[1] = 250                     # == rows[0]
+    bad[8] = -3
+    bad[14] = 100000
+    off = torch.zeros(13, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.tensor(lens), 0)
+    state = torch.zeros(750, device="cuda")
+    gout = torch.randn(B, 24, generator=g)
+    ws = tbe.alloc_workspace(B, 16)
+    tbe.backward_rowwise_adagrad(gout.cuda(), bad.cuda(), off.cuda(), B, flat, state, ws, lr=0.1, eps=1e-8)
+    assert tbe.poll_index_error()
+    keep = torch.ones(16, dtype=torch.bool)
+    keep[[1, 8, 14]] = False
+    lens2 = [1, 1, 0, 3, 1, 1, 1, 1, 0, 2, 1, 1]
+    off2 = np.concatenate([[0], np.cumsum(lens2)])
+    tabs = [flat_cpu[t * 2000:(t + 1) * 2000].view(250, 8).numpy().copy() for t in range(3)]
+    st = np.zeros(750, dtype=np.float32)
+    res = oracle.backward_rowwise_adagrad(tabs, st, gout.numpy(), good[keep].numpy(), off2, B, "sum", 0.1, 1e-8, 1.0)
+    np.testing.assert_allclose(flat.cpu().numpy(), np.concatenate([t.reshape(-1) for t in tabs]), rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(state.cpu().numpy(), st, rtol=1e-5)
+    dbg = tbe.debug_sorted(ws, B, 16)
+    uq = dbg["unique_rows"].numpy()
+    assert sorted(uq[uq < 750].tolist()) == res.unique_rows.tolist()      # the valid rows, each once
+    assert (uq == 750).sum() == 3                                         # one pseudo-row per table that saw an invalid id
+    # offsets that are not ascending: nothing may fault, the call returns, results are unspecified
+    wrong = off.clone()
+    wrong[4], wrong[8] = 14, 3
+    flat2 = flat_cpu.cuda()
+    tbe.backward_rowwise_adagrad(gout.cuda(), good.cuda(), wrong.cuda(), B, flat2, state, ws, lr=0.1, eps=1e-8)
+    torch.cuda.synchronize()
+    assert torch.isfinite(flat2).all()
+    tbe.poll_index_error()
+    tbe.close()
