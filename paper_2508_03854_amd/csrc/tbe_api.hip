@@ -54,6 +54,9 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
     w.tickets = take(4 * (size_t)kTicketWords);   // directly behind long_tables: one loop clears both
     w.seq_gbase = take(8 * (size_t)(h->T + 1));
+    w.dense_rows = take(4 * 16 * (size_t)h->T);            // kDenseRows per table
+    w.dense_n = take(4 * (size_t)h->T);
+    w.dense_bounds = take(4 * 16 * 33 * (size_t)h->T);     // kDenseRows x (kDenseChunks + 1) per table
     w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);

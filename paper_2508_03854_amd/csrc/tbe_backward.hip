@@ -79,6 +79,9 @@ struct SegArgs {
     uint32_t* tcount;      // [T+1] long rows per table (then tbase [T+1], tfill [T+1] behind it)
     uint2* unit_list;      // [cap_units] (position in long_list, unit index)
     uint32_t* bounds;      // [cap_long][kMaxSlices + 1] sub-slice borders inside a sliced row's segment
+    uint32_t* dense_rows;  // [T][kDenseRows] position in long_list of the table's dense rows
+    uint32_t* dense_n;     // [T] number of dense rows (0: the table does not take the dense path)
+    uint32_t* dense_bounds;  // [T][kDenseRows][kDenseChunks + 1] borders of the bag chunks inside each dense row's segment
     uint32_t* tickets;     // [sweep][XCD] counters, kTicketStride words apart, zero before the first sweep
     uint32_t cap_units;
     uint32_t cap_long, cap_chunks;
@@ -224,6 +227,10 @@ constexpr int kMaxPartsSeq = 1024;
 constexpr uint32_t kSliceBytes = (uint32_t)TBE_SLICE_KB << 10;
 
 constexpr uint32_t kSlicedFlag = 0x80000000u;
+constexpr uint32_t kDenseFlag = 0x40000000u;   // the row is reduced by the dense-row kernel: no units, kDenseChunks partial sums
+constexpr int kDenseRows = 16;                 // dense rows per table
+constexpr int kDenseChunks = 32;               // bag chunks (= partial sums) per dense row
+constexpr int kDenseMaxCand = 1024;            // candidates per table the selection can rank
 
 // number of sub-slices of a table's gradient block (power of two); >= 8 means "bag-sliced over the XCDs"
 __device__ __host__ __forceinline__ uint32_t slices_for(uint32_t B, uint32_t D) {
@@ -344,7 +351,8 @@ __global__ __launch_bounds__(1024) void seg_long_units_kernel(const SegArgs a, u
     uint32_t carry = 0;
     for (uint32_t base = 0; base < nlong; base += 1024) {
         const uint32_t pos = base + threadIdx.x;
-        const uint32_t C = pos < nlong ? (list[pos].z & ~kSlicedFlag) : 0u;
+        const uint32_t z = pos < nlong ? list[pos].z : 0u;
+        const uint32_t C = (z & kDenseFlag) ? 0u : (z & ~kSlicedFlag);   // dense rows have no units
         uint32_t tot;
         const uint32_t ex = block_excl_scan<1024>(C, smem, &tot);
         for (uint32_t c = 0; c < C; ++c) {
@@ -477,6 +485,197 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
             const uint32_t e = first + k * kWpb + (threadIdx.x >> 6);
             if (e < nunits) long_unit<NC, MEAN, GT>(a, sweep, xcd, e);   // the last ticket may be partly empty
         }
+    }
+}
+
+// ---- 2b. dense rows ------------------------------------------------------------------------------------------
+// The few hottest rows of a table appear in a large share of its bags (at Zipf exponents around 1.1 a dozen rows
+// take a third of all lookups).  Reducing them lookup by lookup reads every bag's gradient row once per hot row that
+// the bag holds; instead, the table's gradient block is streamed ONCE, bag by bag, and every gradient row is added
+// to the accumulators of all the table's dense rows, weighted by how often the bag holds that row (mostly 0 or 1).
+// A wavefront owns one bag chunk of one table: it keeps kDenseRows x D accumulators in registers, walks its bags in
+// blocks of 64, builds the 64 x kDenseRows count table of a block in LDS from the rows' sorted bag lists (a cursor
+// per row; the lists are ascending), and ends with one partial sum per dense row.  seg_long_update adds the
+// kDenseChunks partial sums of a row in chunk order, so the result does not depend on scheduling.
+// Selection (one workgroup per table): rows with at least max(kHeavyMin, B/4) lookups, the kDenseRows longest (ties:
+// smaller key first), and only if together they hold at least 2*B lookups - otherwise streaming the whole block
+// costs more than the lookups it saves.  Only bag-sliced tables qualify (others fit the L2 anyway).
+__global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, const uint32_t* __restrict__ tbase) {
+    __shared__ uint32_t c_len[kDenseMaxCand], c_key[kDenseMaxCand], c_pos[kDenseMaxCand], c_rank[kDenseMaxCand];
+    __shared__ uint32_t s_n, s_sum;
+    const int t = blockIdx.x;
+    uint4* list = reinterpret_cast<uint4*>(a.long_list);
+    const uint32_t D = (uint32_t)(a.D_off[t + 1] - a.D_off[t]);
+    if (threadIdx.x == 0) {
+        s_n = 0u;
+        s_sum = 0u;
+        a.dense_n[t] = 0u;
+    }
+    __syncthreads();
+    if (a.seq || slices_for((uint32_t)a.B, D) < 8u) return;
+    const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
+    const uint32_t i0 = tbase[t] < nlong ? tbase[t] : nlong, i1 = tbase[t + 1] < nlong ? tbase[t + 1] : nlong;
+    const uint32_t thr = (uint32_t)a.B / 4u > kHeavyMin ? (uint32_t)a.B / 4u : kHeavyMin;
+    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
+        const uint4 ent = list[i];
+        if (!(ent.z & kSlicedFlag)) continue;
+        const uint32_t len = a.seg_start[ent.x + 1] - a.seg_start[ent.x];
+        if (len < thr) continue;
+        const uint32_t j = atomicAdd(&s_n, 1u);
+        if (j < (uint32_t)kDenseMaxCand) {
+            c_len[j] = len;
+            c_key[j] = a.keys_unique[ent.x];
+            c_pos[j] = i;
+        }
+    }
+    __syncthreads();
+    const uint32_t n = s_n;
+    if (n == 0u || n > (uint32_t)kDenseMaxCand) return;   // (more candidates than can be ranked: all stay sparse)
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < n; ++j)
+            rank += (c_len[j] > c_len[i] || (c_len[j] == c_len[i] && c_key[j] < c_key[i])) ? 1u : 0u;
+        c_rank[i] = rank;
+        if (rank < (uint32_t)kDenseRows) atomicAdd(&s_sum, c_len[i] < 0x08000000u ? c_len[i] : 0x08000000u);
+    }
+    __syncthreads();
+    if (s_sum < 2u * (uint32_t)a.B) return;
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+        if (c_rank[i] < (uint32_t)kDenseRows) {
+            a.dense_rows[t * kDenseRows + c_rank[i]] = c_pos[i];
+            a.long_list[4 * (size_t)c_pos[i] + 2] = kDenseFlag;
+        }
+    }
+    if (threadIdx.x == 0) a.dense_n[t] = n < (uint32_t)kDenseRows ? n : (uint32_t)kDenseRows;
+}
+
+// borders of the bag chunks inside every dense row's segment: one wavefront per row, one border per lane
+__global__ __launch_bounds__(kSegThreads) void seg_dense_bounds_kernel(const SegArgs a) {
+    const int t = blockIdx.x;
+    const uint32_t n = a.dense_n[t];
+    if (n == 0u) return;
+    const int lane = lane_id();
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
+    const uint32_t CB = ((uint32_t)a.B + kDenseChunks - 1) / kDenseChunks;
+    const uint32_t bag0 = (uint32_t)t * (uint32_t)a.B;
+    for (uint32_t h = threadIdx.x >> 6; h < n; h += kSegThreads / kWave) {
+        const uint4 ent = list[a.dense_rows[t * kDenseRows + h]];
+        const uint32_t s = a.seg_start[ent.x], e = a.seg_start[ent.x + 1];
+        for (int c = lane; c <= kDenseChunks; c += kWave) {
+            uint32_t r;
+            if (c == 0) r = s;
+            else if (c == kDenseChunks) r = e;
+            else {
+                const uint32_t b = (uint32_t)c * CB < (uint32_t)a.B ? (uint32_t)c * CB : (uint32_t)a.B;
+                r = lower_bound_u32(a.bag_sorted, s, e, bag0 + b);
+            }
+            a.dense_bounds[((size_t)t * kDenseRows + h) * (kDenseChunks + 1) + c] = r;
+        }
+    }
+}
+
+constexpr int kDenseU = 2;   // gradient rows in flight per lane group
+template <bool MEAN, typename GT>
+__global__ __launch_bounds__(kSegThreads, 3) void seg_dense_partial_kernel(const SegArgs a) {
+    __shared__ uint32_t s_cnt[kSegThreads / kWave][kWave][kDenseRows];   // per wavefront: counts of a block of 64 bags
+    const int lane = lane_id();
+    const int wv = threadIdx.x >> 6;
+    const uint32_t wid = blockIdx.x * (kSegThreads / kWave) + (uint32_t)wv;
+    const int t = (int)(wid / kDenseChunks);
+    const uint32_t c = wid % kDenseChunks;
+    if (t >= a.T) return;
+    const uint32_t n = a.dense_n[t];
+    if (n == 0u) return;   // (wavefronts leave on their own: the kernel uses no workgroup barrier)
+    const int d0 = a.D_off[t];
+    const RowGeom g = row_geom(a.D_off[t + 1] - d0);
+    const uint32_t B = (uint32_t)a.B;
+    const uint32_t CB = (B + kDenseChunks - 1) / kDenseChunks;
+    const uint32_t b_lo = c * CB < B ? c * CB : B;
+    const uint32_t b_hi = b_lo + CB < B ? b_lo + CB : B;
+    const uint32_t bag0 = (uint32_t)t * B;
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
+    // lane h < n: cursor into dense row h's sorted bag list, the end of this chunk's part, the row's first slot
+    uint32_t cur = 0, end = 0, slot0 = 0;
+    if ((uint32_t)lane < n) {
+        const size_t o = ((size_t)t * kDenseRows + lane) * (kDenseChunks + 1) + c;
+        cur = a.dense_bounds[o];
+        end = a.dense_bounds[o + 1];
+        slot0 = list[a.dense_rows[t * kDenseRows + lane]].y;
+    }
+    float acc[kDenseRows][4];
+#pragma unroll
+    for (int h = 0; h < kDenseRows; ++h) acc[h][0] = acc[h][1] = acc[h][2] = acc[h][3] = 0.f;
+    const GT* gcol = static_cast<const GT*>(a.grad_out) + d0 + g.lc;
+    const bool col_on = g.lc < g.D;
+    uint32_t* cnt = &s_cnt[wv][0][0];
+    for (uint32_t sb = b_lo; sb < b_hi; sb += kWave) {
+        const uint32_t nb = b_hi - sb < (uint32_t)kWave ? b_hi - sb : (uint32_t)kWave;
+        // ---- the block's count table: zero, then one pass per dense row over the part of its list inside the block
+#pragma unroll
+        for (int q = 0; q < kDenseRows; q += 4)
+            *reinterpret_cast<uint4*>(&cnt[lane * kDenseRows + q]) = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (uint32_t h = 0; h < n; ++h) {
+            uint32_t ch = __shfl(cur, (int)h, kWave);
+            const uint32_t eh = __shfl(end, (int)h, kWave);
+            for (;;) {   // the list is ascending, so the entries of this block are a prefix of what is left
+                const uint32_t ei = ch + (uint32_t)lane;
+                const uint32_t v = ei < eh ? a.bag_sorted[ei] - bag0 - sb : 0xFFFFFFFFu;
+                const bool inb = v < nb;
+                if (inb) atomicAdd(&cnt[v * kDenseRows + h], 1u);
+                const uint32_t k = (uint32_t)__popcll(__ballot(inb));
+                ch += k;
+                if (k < (uint32_t)kWave) break;
+            }
+            if ((uint32_t)lane == h) cur = ch;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        float my_s = 1.f;
+        if (MEAN && (uint32_t)lane < nb) my_s = bag_scale<true>(a.offsets, bag0 + sb + (uint32_t)lane);
+        // ---- stream the block's gradient rows; every lane group takes every G-th bag
+        for (uint32_t k0 = 0; k0 < nb; k0 += kDenseU * g.G) {
+            typename GradIO<GT>::raw_t x[kDenseU];
+            uint32_t kk[kDenseU];
+#pragma unroll
+            for (int u = 0; u < kDenseU; ++u) {
+                kk[u] = k0 + (uint32_t)(u * g.G + g.sub);
+                const bool on = kk[u] < nb && col_on;
+                x[u] = on ? GradIO<GT>::load(gcol + (int64_t)(sb + kk[u]) * a.sumD) : GradIO<GT>::zero();
+            }
+#pragma unroll
+            for (int u = 0; u < kDenseU; ++u) {
+                const uint32_t k = kk[u] & (kWave - 1);   // (a bag beyond nb has a zero gradient fragment and zero counts)
+                float4 f = GradIO<GT>::to_float(x[u]);
+                if (MEAN) {
+                    const float sc = __shfl(my_s, (int)k, kWave);
+                    f.x *= sc; f.y *= sc; f.z *= sc; f.w *= sc;
+                }
+                uint32_t w[kDenseRows];
+#pragma unroll
+                for (int q = 0; q < kDenseRows; q += 4) {
+                    const uint4 r = *reinterpret_cast<const uint4*>(&cnt[k * kDenseRows + q]);
+                    w[q] = r.x; w[q + 1] = r.y; w[q + 2] = r.z; w[q + 3] = r.w;
+                }
+#pragma unroll
+                for (int h = 0; h < kDenseRows; ++h) {
+                    const float m = (float)w[h];
+                    acc[h][0] = fmaf(m, f.x, acc[h][0]);
+                    acc[h][1] = fmaf(m, f.y, acc[h][1]);
+                    acc[h][2] = fmaf(m, f.z, acc[h][2]);
+                    acc[h][3] = fmaf(m, f.w, acc[h][3]);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the reads above precede the next block's zeroing
+    }
+    // ---- one partial sum per dense row: fold the lane groups, then the first group stores
+#pragma unroll
+    for (int h = 0; h < kDenseRows; ++h) {
+        float one[1][4] = {{acc[h][0], acc[h][1], acc[h][2], acc[h][3]}};
+        fold_groups<1>(one, g);
+        const uint32_t slot = __shfl(slot0, h, kWave) + c;
+        if ((uint32_t)h < n && g.sub == 0 && col_on)
+            *reinterpret_cast<float4*>(a.partial + (size_t)slot * a.maxD + g.lc) = make_float4(one[0][0], one[0][1], one[0][2], one[0][3]);
     }
 }
 
@@ -651,7 +850,8 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
         const int D = a.D_off[t + 1] - a.D_off[t];
         const uint32_t C = ent.z & ~kSlicedFlag;
         uint32_t nch = C;  // partial sums of the row
-        if (ent.z & kSlicedFlag) nch = C == 1u ? 8u : C * (slices_for((uint32_t)a.B, (uint32_t)D));
+        if (ent.z & kDenseFlag) nch = kDenseChunks;
+        else if (ent.z & kSlicedFlag) nch = C == 1u ? 8u : C * (slices_for((uint32_t)a.B, (uint32_t)D));
         // here all 64 lanes cover the row (or a 256-column part of it); groups are not used
         RowGeom g;
         g.D = D; g.LPR = kWave; g.G = 1; g.sub = 0; g.lc = lane_id() * 4;
@@ -754,6 +954,12 @@ __global__ void seq_gbase_kernel(const IdxView offsets, const int32_t* __restric
     }
 }
 
+template <typename GT>
+static void launch_dense_partial(const SegArgs& a, unsigned grid, bool mean, hipStream_t s) {
+    if (mean) seg_dense_partial_kernel<true, GT><<<grid, kSegThreads, 0, s>>>(a);
+    else seg_dense_partial_kernel<false, GT><<<grid, kSegThreads, 0, s>>>(a);
+}
+
 hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* ws, int spare, const void* grad_out,
                                  int grad_io, const void* offsets, int idx32, int32_t B, tbe_pooling pooling, float lr,
                                  float eps, float c, void* tables, float* state, int seq, int64_t grad_elems, hipStream_t s) {
@@ -789,12 +995,17 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.unit_list = reinterpret_cast<uint2*>(ws + w.unit_list);
     a.bounds = reinterpret_cast<uint32_t*>(ws + w.bounds);
     a.tickets = reinterpret_cast<uint32_t*>(ws + w.tickets);
+    a.dense_rows = reinterpret_cast<uint32_t*>(ws + w.dense_rows);
+    a.dense_n = reinterpret_cast<uint32_t*>(ws + w.dense_n);
+    a.dense_bounds = reinterpret_cast<uint32_t*>(ws + w.dense_bounds);
     a.cap_units = (uint32_t)w.cap_units;
     a.cap_long = (uint32_t)w.cap_long;
     a.cap_chunks = (uint32_t)w.cap_chunks;
     const bool mean = pooling == TBE_MEAN;
     const bool f32 = h->dtype == TBE_F32;
     const bool narrow = h->maxD <= 256;
+    // the dense-row path: narrow tables only, and only when some table's gradient block is bag-sliced at all
+    const bool dense = narrow && !seq && slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u;
     uint32_t* tcount = reinterpret_cast<uint32_t*>(ws + w.long_tables);
     uint32_t* tbase = tcount + (h->T + 1);
     uint32_t* tfill = tbase + (h->T + 1);
@@ -811,8 +1022,18 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         LaunchTimer tm(h, s, "seg_long_list");
         seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
         seg_long_fill_kernel<<<64, 256, 0, s>>>(a, counters, tbase, tfill);
+        if (dense) seg_dense_select_kernel<<<h->T, 256, 0, s>>>(a, tbase);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
         if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<256, kSegThreads, 0, s>>>(a);
+        if (dense) seg_dense_bounds_kernel<<<h->T, kSegThreads, 0, s>>>(a);
+        tm.done();
+    }
+    if (dense) {
+        LaunchTimer tm(h, s, "seg_dense_partial");
+        const unsigned grid = (unsigned)(((int64_t)h->T * kDenseChunks + kSegThreads / kWave - 1) / (kSegThreads / kWave));
+        if (grad_io == 0) launch_dense_partial<float>(a, grid, mean, s);
+        else if (grad_io == 1) launch_dense_partial<__half>(a, grid, mean, s);
+        else launch_dense_partial<bf16_t>(a, grid, mean, s);
         tm.done();
     }
     {

@@ -73,7 +73,7 @@ struct Workspace {
     // (pooled calls) or its position (non-pooled calls), so vals[sorted] is the per-lookup stream the gradient
     // kernels read.  After the sort vals[spare] receives unique_rows.
     size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, seg_bounds,
-        seg_chunk0, chunk_desc, raw_long,
+        seg_chunk0, chunk_desc, dense_rows, dense_n, dense_bounds, raw_long,
         long_list, unit_list, bounds, partial, total;
     int radix_blocks;     // blocks a single segment of N keys would need
     int radix_maxc;       // chunk descriptors: radix_blocks + number of segments (every segment may end in a partial chunk)

@@ -390,3 +390,21 @@ def test_segmented_sort_invalid_ids_and_malformed_offsets():
     assert torch.isfinite(flat2).all()
     tbe.poll_index_error()
     tbe.close()
+
+
+# ---- the hottest rows of a bag-sliced table: reduced by streaming the table's gradient block once ---------------
+@pytest.mark.parametrize("dtype,pooling", [("f32", "sum"), ("f16", "mean")])
+def test_dense_rows_path(H, dtype, pooling):
+    rng = np.random.default_rng(11)
+    B = 32768                                   # B * D * 4 = 8 MB per table: sliced over the XCDs
+    cfg = make_cfg([6, 5000, 40], [64, 64, 128], dtype=dtype, B=B, pooling=pooling, c=2.0)
+    lens = np.concatenate([rng.integers(2, 7, size=B),       # table 0: six rows, all of them hit ~20000 times
+                           rng.integers(0, 41, size=B),      # table 1: 24 hot rows (more than one pass takes) + a tail
+                           rng.integers(0, 3, size=B)])      # table 2: 40 rows with ~800 hits: long, but not dense
+    n0, n1, n2 = (int(lens[t * B:(t + 1) * B].sum()) for t in range(3))
+    hot = rng.integers(0, 24, size=n1)
+    tail = rng.integers(24, 5000, size=n1)
+    ids1 = np.where(rng.random(n1) < 0.9, hot * 7 % 5000, tail)     # hot rows scattered over the key range
+    ids = np.concatenate([rng.integers(0, 6, size=n0), ids1, rng.integers(0, 40, size=n2)])
+    reps = run_custom(H, cfg, lens, ids, steps=2)
+    assert reps[0]["max_seg"] > 20000
