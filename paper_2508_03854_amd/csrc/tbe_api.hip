@@ -46,7 +46,9 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     // partial sums of a long row (> kSegChunk lookups): 8 (one per XCD, 8 <= len/64), or for rows of >= 8192
     // lookups at most len/256 + 128 <= len/256 + len/64, or ceil(len/kSegChunk) <= 2*len/kSegChunk equal shares
     w.cap_long = (int64_t)n / (kSegChunk + 1) + 1;
-    w.cap_chunks = (int64_t)n / 64 + (int64_t)n / 256 + 2 * ((int64_t)n / kSegChunk) + 2;
+    // plus kDenseChunks fresh slots for every dense row (at most kDenseRows per table) that had been given 8
+    w.cap_chunks = (int64_t)n / 64 + (int64_t)n / 256 + 2 * ((int64_t)n / kSegChunk) + 2 +
+                   (int64_t)kDenseChunks * kDenseRows * h->T;
     // work units: one per long row, or len/(8*256) + 2 <= len/1024 for the heaviest, or ceil(len/512) <= len/256 shares
     w.cap_units = w.cap_long + (int64_t)n / 1024 + (int64_t)n / 256 + 2;
     w.unit_list = take(8 * (size_t)w.cap_units);
@@ -54,9 +56,9 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
     w.tickets = take(4 * (size_t)kTicketWords);   // directly behind long_tables: one loop clears both
     w.seq_gbase = take(8 * (size_t)(h->T + 1));
-    w.dense_rows = take(4 * 16 * (size_t)h->T);            // kDenseRows per table
+    w.dense_rows = take(4 * (size_t)kDenseRows * (size_t)h->T);
     w.dense_n = take(4 * (size_t)h->T);
-    w.dense_bounds = take(4 * 16 * 33 * (size_t)h->T);     // kDenseRows x (kDenseChunks + 1) per table
+    w.dense_bounds = take(4 * (size_t)kDenseRows * (kDenseChunks + 1) * (size_t)h->T);
     w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);

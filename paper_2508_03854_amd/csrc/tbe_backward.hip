@@ -60,6 +60,7 @@ struct SegArgs {
     const uint32_t* keys_unique;  // unique_rows
     const uint32_t* seg_start;
     const uint32_t* counters;     // [0]=U, [1]=n_long, [2]=n_chunks
+    uint32_t* counters_rw;        // the same words, for the kernels that bump them
     const uint32_t* bag_sorted;   // linear bag id of every sorted position
     IdxView offsets;
     const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT (or the sequence layout)
@@ -228,8 +229,11 @@ constexpr uint32_t kSliceBytes = (uint32_t)TBE_SLICE_KB << 10;
 
 constexpr uint32_t kSlicedFlag = 0x80000000u;
 constexpr uint32_t kDenseFlag = 0x40000000u;   // the row is reduced by the dense-row kernel: no units, kDenseChunks partial sums
-constexpr int kDenseRows = 16;                 // dense rows per table
-constexpr int kDenseChunks = 32;               // bag chunks (= partial sums) per dense row
+#ifndef TBE_DENSE_DIV
+#define TBE_DENSE_DIV 8
+#endif
+constexpr uint32_t kDenseDiv = TBE_DENSE_DIV;   // a dense row has at least B / kDenseDiv lookups (and at least kDenseMin)
+constexpr uint32_t kDenseMin = 4096;
 constexpr int kDenseMaxCand = 1024;            // candidates per table the selection can rank
 
 // number of sub-slices of a table's gradient block (power of two); >= 8 means "bag-sliced over the XCDs"
@@ -497,25 +501,27 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
 // blocks of 64, builds the 64 x kDenseRows count table of a block in LDS from the rows' sorted bag lists (a cursor
 // per row; the lists are ascending), and ends with one partial sum per dense row.  seg_long_update adds the
 // kDenseChunks partial sums of a row in chunk order, so the result does not depend on scheduling.
-// Selection (one workgroup per table): rows with at least max(kHeavyMin, B/4) lookups, the kDenseRows longest (ties:
+// Selection (one workgroup per table): rows with at least max(kDenseMin, B/kDenseDiv) lookups, the kDenseRows longest (ties:
 // smaller key first), and only if together they hold at least 2*B lookups - otherwise streaming the whole block
 // costs more than the lookups it saves.  Only bag-sliced tables qualify (others fit the L2 anyway).
 __global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, const uint32_t* __restrict__ tbase) {
     __shared__ uint32_t c_len[kDenseMaxCand], c_key[kDenseMaxCand], c_pos[kDenseMaxCand], c_rank[kDenseMaxCand];
-    __shared__ uint32_t s_n, s_sum;
+    __shared__ uint32_t s_n, s_sum, s_need, s_base;
     const int t = blockIdx.x;
     uint4* list = reinterpret_cast<uint4*>(a.long_list);
     const uint32_t D = (uint32_t)(a.D_off[t + 1] - a.D_off[t]);
     if (threadIdx.x == 0) {
         s_n = 0u;
         s_sum = 0u;
+        s_need = 0u;
+        s_base = 0u;
         a.dense_n[t] = 0u;
     }
     __syncthreads();
     if (a.seq || slices_for((uint32_t)a.B, D) < 8u) return;
     const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
     const uint32_t i0 = tbase[t] < nlong ? tbase[t] : nlong, i1 = tbase[t + 1] < nlong ? tbase[t + 1] : nlong;
-    const uint32_t thr = (uint32_t)a.B / 4u > kHeavyMin ? (uint32_t)a.B / 4u : kHeavyMin;
+    const uint32_t thr = (uint32_t)a.B / kDenseDiv > kDenseMin ? (uint32_t)a.B / kDenseDiv : kDenseMin;
     for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
         const uint4 ent = list[i];
         if (!(ent.z & kSlicedFlag)) continue;
@@ -540,9 +546,22 @@ __global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, 
     }
     __syncthreads();
     if (s_sum < 2u * (uint32_t)a.B) return;
+    // a selected row below kHeavyMin was given 8 partial slots only: such rows take kDenseChunks fresh ones (where
+    // they lie does not matter, the sums are added in chunk order); one allocation for the table
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x)
+        if (c_rank[i] < (uint32_t)kDenseRows && (a.long_list[4 * (size_t)c_pos[i] + 2] & ~kSlicedFlag) == 1u) atomicAdd(&s_need, 1u);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        s_base = s_need ? atomicAdd(&a.counters_rw[2], s_need * (uint32_t)kDenseChunks) : 0u;
+        s_need = 0u;
+    }
+    __syncthreads();
+    if (s_base + (uint32_t)kDenseRows * kDenseChunks > a.cap_chunks) return;   // never true: the capacity reserves these
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
         if (c_rank[i] < (uint32_t)kDenseRows) {
             a.dense_rows[t * kDenseRows + c_rank[i]] = c_pos[i];
+            if ((a.long_list[4 * (size_t)c_pos[i] + 2] & ~kSlicedFlag) == 1u)
+                a.long_list[4 * (size_t)c_pos[i] + 1] = s_base + atomicAdd(&s_need, 1u) * (uint32_t)kDenseChunks;
             a.long_list[4 * (size_t)c_pos[i] + 2] = kDenseFlag;
         }
     }
@@ -576,7 +595,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_dense_bounds_kernel(const Seg
 
 constexpr int kDenseU = 2;   // gradient rows in flight per lane group
 template <bool MEAN, typename GT>
-__global__ __launch_bounds__(kSegThreads, 3) void seg_dense_partial_kernel(const SegArgs a) {
+__global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_dense_partial_kernel(const SegArgs a) {
     __shared__ uint32_t s_cnt[kSegThreads / kWave][kWave][kDenseRows];   // per wavefront: counts of a block of 64 bags
     const int lane = lane_id();
     const int wv = threadIdx.x >> 6;
@@ -971,6 +990,7 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     a.counters = counters;
+    a.counters_rw = counters;
     if (seq)
         seq_gbase_kernel<<<1, 64, 0, s>>>(IdxView{offsets, idx32}, h->d_D_off, h->T, (int64_t)w.n, grad_elems,
                                           reinterpret_cast<int64_t*>(ws + w.seq_gbase), counters, h->d_err);

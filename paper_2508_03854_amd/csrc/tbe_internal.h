@@ -24,6 +24,11 @@ constexpr int kRleTile = 2048;         // elements per run-length tile
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
 constexpr int kMaxSortSegments = 4096;  // tables beyond this are sorted as one segment on the linearised key
+#ifndef TBE_DENSE_ROWS
+#define TBE_DENSE_ROWS 16
+#endif
+constexpr int kDenseRows = TBE_DENSE_ROWS;   // rows per table that the dense-row kernel reduces (multiple of 4)
+constexpr int kDenseChunks = 32;            // bag chunks (= partial sums) per dense row
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
