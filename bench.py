@@ -66,13 +66,15 @@ def algorithmic_bytes(cfg, nnz, U_t, ib=8, eb=4):
     dense = cfg.B * cfg.sum_D * eb      # eb bytes per element of out / grad_out, ib bytes per id and offset
     return {
         "forward_pool": rows_bytes + nnz * ib + nb * ib + dense,
-        "linearize": nnz * ib + nb * ib + nnz * 12,                # ids + offsets in; key, position, bag out
+        "linearize": nnz * ib + nb * ib + nnz * 8,                 # ids + offsets in; key and bag id out
         "radix_hist": nnz * 4,
-        "radix_scatter": nnz * 16,                                  # (key, position) in and out
+        "radix_plan": 0,
+        "radix_scatter": nnz * 16,                                  # (key, bag id) in and out
         "radix_binscan": 0,
         "rle_count": nnz * 4,
         "rle_scan": 0,
         "rle_write": nnz * 4 + U * 8,
+        "seg_dense_partial": dense,                                 # streams the gradient block of every table once
         "seg_long_list": U * 8,
         # gradient once, sorted positions and their bags, row + moment read-modify-write per unique row
         "seg_update": dense + nnz * 8 + U * 8 + 2 * rows_bytes + 8 * U,

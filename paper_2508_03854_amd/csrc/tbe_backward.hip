@@ -26,7 +26,7 @@ constexpr int kSegUnroll = TBE_SEG_U;
 #define TBE_LONG_BLOCKS 2048
 #endif
 #ifndef TBE_SLICE_KB
-#define TBE_SLICE_KB 1024
+#define TBE_SLICE_KB 512
 #endif
 
 struct RowGeom {
@@ -217,7 +217,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
 // one XCD's 4 MB L2, so the slices that hot rows gather would stream through the L2 again and again
 // (measured: random 1 KB reads run at ~28 TB/s from an L2-resident set, ~8 TB/s otherwise).  For such tables
 // every XCD owns one eighth of the bags (workgroup id mod 8 is the XCD the dispatcher picks) and walks it in
-// sub-slices of at most ~1 MB of gradient, one sub-slice per sweep over the list of hot rows; the hot rows are
+// sub-slices of at most ~0.5 MB of gradient, one sub-slice per sweep over the list of hot rows; the hot rows are
 // listed table by table, so at any time an XCD works on one sub-slice of one or two tables, which stays
 // resident in its L2 while all hot rows of the table pass over it.  The stable sort left a row's lookups in
 // ascending bag order, so the lookups of a sub-slice are one contiguous range found by binary search.
