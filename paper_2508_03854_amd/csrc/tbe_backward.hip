@@ -61,7 +61,7 @@ struct SegArgs {
     const uint32_t* seg_start;
     const uint32_t* counters;     // [0]=U, [1]=n_long, [2]=n_chunks
     uint32_t* counters_rw;        // the same words, for the kernels that bump them
-    const uint32_t* bag_sorted;   // linear bag id of every sorted position
+    const uint32_t* bag_sorted;   // the sorted payload: linear bag id of every sorted lookup
     IdxView offsets;
     const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT (or the sequence layout)
     const int64_t* seq_gbase;     // non-pooled mode only: element offset of table t's gradient block minus start_t * D_t

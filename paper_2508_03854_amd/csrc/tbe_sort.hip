@@ -1,13 +1,13 @@
-// Integer half of the backward pass: linearise ids into row keys, stable LSD radix sort of (key, position),
-// run-length segmentation into unique rows.  Everything here is exact integer work.
+// Integer half of the backward pass: linearise ids into row keys, stable LSD radix sort of (key, payload) with the
+// lookup's bag id (pooled calls) or position (non-pooled calls) as payload, run-length segmentation into unique rows.  Everything here is exact integer work.
 #include "tbe_device.cuh"
 #include "tbe_internal.h"
 
 namespace tbe {
 
 // =================================================================================================
-// linearize: key[p] = row_base[t(p)] + indices[p], bag_of_pos[p] = linear bag id of p
-// (the sort payload of position p is p itself; the first radix pass generates it instead of reading it)
+// linearize: key[p] = row_base[t(p)] + indices[p] (or the table-local id alone when the sort is segmented),
+// bag_of_pos[p] = linear bag id of p, the payload a pooled call sorts along with the key
 // =================================================================================================
 constexpr int kLinThreads = 256;
 
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
             key = local_keys ? (uint32_t)R : invalid_key;
             atomicOr(err, 1);
         }
-        keys[p] = key;                  // the payload of position p is p itself: the first sort pass generates it
+        keys[p] = key;
         bag_of_pos[p] = (uint32_t)bag;
     }
 }
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
             const int64_t i = wbase + k * kWave + lane;
             const bool valid = i < e;
             key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
-            val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // first pass: payload = position
+            val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // iota: the payload is the position itself
         }
         // rank inside the wave, item by item in input order: peers = valid lanes holding the same digit
 #pragma unroll
