@@ -22,15 +22,20 @@ __device__ __forceinline__ int64_t upper_bound_i64(const IdxView a, int64_t lo, 
 }
 
 // A block owns kLinTile consecutive positions.  It finds the bags that own its first and last position
-// with two binary searches in the global offsets, stages that offsets segment in LDS (relative to the
-// tile start), and every thread then finds the bag of its position with a short search in LDS.
+// with two binary searches in the global offsets and stages that offsets segment in LDS (relative to the
+// tile start).  Every bag that starts inside the tile then marks its first position, and a running maximum
+// over the positions gives each position the last bag that starts at or before it, i.e. its owner (empty bags
+// start where the next one does and lose against it).
 __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView indices, const IdxView offsets,
                                                                 const int64_t nbags, const int32_t B,
                                                                 const int64_t* __restrict__ row_base,
                                                                 const uint32_t invalid_key, const bool local_keys,
                                                                 const int64_t N, uint32_t* __restrict__ keys,
                                                                 uint32_t* __restrict__ bag_of_pos, int32_t* err) {
+    constexpr int kItems = kLinTile / kLinThreads;   // positions per thread: kItems rows of 64 per wavefront
     __shared__ int32_t s_off[kLinTile + 2];
+    __shared__ int32_t s_own[kLinTile];
+    __shared__ int32_t s_wmax[kLinThreads / kWave];
     __shared__ int64_t s_lo, s_hi;
     const int64_t p0 = (int64_t)blockIdx.x * kLinTile;
     const int64_t p1 = (p0 + kLinTile < N) ? p0 + kLinTile : N;
@@ -45,6 +50,7 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
         s_lo = lo;
         s_hi = hi;
     }
+    for (int i = threadIdx.x; i < kLinTile; i += kLinThreads) s_own[i] = 0;
     __syncthreads();
     const int64_t lo = s_lo, hi = s_hi;
     const int64_t nb = hi - lo + 1;             // bags touched by this tile (>= 1)
@@ -54,23 +60,41 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
             int64_t rel = offsets[lo + i] - p0;
             rel = rel < -1 ? -1 : (rel > kLinTile ? kLinTile : rel);
             s_off[i] = (int32_t)rel;
+            if (i >= 1 && i < (int)nb && rel >= 0 && rel < kLinTile) atomicMax(&s_own[rel], i);   // bag lo+i starts here
         }
     }
     __syncthreads();
-    for (int64_t p = p0 + threadIdx.x; p < p1; p += kLinThreads) {
-        int64_t bag;
-        if (staged) {
-            const int32_t rel = (int32_t)(p - p0);
-            int a = 0, b = (int)nb;  // first i in [0, nb] with s_off[i] > rel; s_off[nb] > rel for well-formed input
-            while (a < b) {
-                const int mid = (a + b) >> 1;
-                if (s_off[mid] > rel) b = mid;
-                else a = mid + 1;
+    const int lane = lane_id();
+    const int w = threadIdx.x >> 6;
+    int32_t own[kItems];
+    if (staged) {
+        // running maximum: along each row of 64 by shuffles, carried from row to row, then across the wavefronts
+        int32_t carry = 0;
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) {
+            int32_t v = s_own[w * (kWave * kItems) + k * kWave + lane];
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int32_t up = __shfl_up(v, o, kWave);
+                if (lane >= o) v = up > v ? up : v;
             }
-            bag = lo + a - 1;
-        } else {  // a tile that spans more than kLinTile bags (long runs of empty bags): search in global memory
-            bag = upper_bound_i64(offsets, lo, hi + 1, p) - 1;
+            v = v > carry ? v : carry;
+            own[k] = v;
+            carry = __shfl(v, kWave - 1, kWave);
         }
+        if (lane == 0) s_wmax[w] = carry;
+        __syncthreads();
+        int32_t prev = 0;
+        for (int ww = 0; ww < w; ++ww) prev = s_wmax[ww] > prev ? s_wmax[ww] : prev;
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) own[k] = own[k] > prev ? own[k] : prev;
+    }
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int64_t p = p0 + w * (kWave * kItems) + k * kWave + lane;
+        if (p >= p1) continue;
+        int64_t bag;
+        if (staged) bag = lo + own[k];
+        else bag = upper_bound_i64(offsets, lo, hi + 1, p) - 1;   // a tile spanning more than kLinTile bags (runs of empty bags)
         bag = bag < lo ? lo : (bag > hi ? hi : bag);
         const int32_t t = (int32_t)(bag / B);
         const int64_t rb = row_base[t];
