@@ -82,7 +82,8 @@ def ulp16_distance(a: np.ndarray, b: np.ndarray) -> np.ndarray:
 
 def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor, tabs, state_np: np.ndarray,
                idx: torch.Tensor, off: torch.Tensor, gout: torch.Tensor, ws: torch.Tensor, check_sorted: bool = True,
-               same_inputs: bool = True, index_dtype: torch.dtype = torch.int64, io: str = "f32"):
+               same_inputs: bool = True, index_dtype: torch.dtype = torch.int64, io: str = "f32",
+               ulp_rate: float = 2e-3):
     """One forward + backward on both sides, in place; compares everything.  Returns a dict of error figures.
     same_inputs: both sides start this step from bit-identical weights (true for the first step).  After a
     step on fp16 tables the two sides may already differ by one binary16 ulp where the fp32 and fp64 results
@@ -169,7 +170,9 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
                 ulp_bad += int((d > 0).sum())
                 ulp_n += d.size
     if ulp_n:
-        assert ulp_bad <= max(2, 2e-3 * ulp_n), f"{ulp_bad}/{ulp_n} fp16 weights round differently from the oracle"
+        # (each such element is exactly one ulp off; how often the fp32 and fp64 results straddle a rounding boundary
+        # depends on how much w and its update cancel, hence a rate the caller may widen for larger learning rates)
+        assert ulp_bad <= max(2, ulp_rate * ulp_n), f"{ulp_bad}/{ulp_n} fp16 weights round differently from the oracle"
         report["fp16_ulp_mismatch_frac"] = ulp_bad / ulp_n
     report["w_max_err"] = werr
     report["v_max_err"] = assert_close(state_gpu[touched], state_np[touched], RTOL_F32, 1e-6, "moments")

@@ -1,0 +1,74 @@
+"""GPU parity on randomly drawn small problems: table counts, row counts, widths, batch sizes, bag-length mixes,
+id skews, weight / index / gradient element types and pooling modes in combinations the fixed workloads do not hit.
+Every case is seeded; the HIP path is compared with the CPU oracle by the shared harness."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+def draw_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "f16" if rng.random() < 0.4 else "f32"
+    dmul = 8 if dtype == "f16" else 4
+    T = int(rng.choice([1, 2, 3, 5, 9, 17, 40]))
+    widths = [dmul * int(x) for x in rng.choice([1, 2, 4, 8, 16, 32], size=T)]
+    if rng.random() < 0.25:
+        widths[int(rng.integers(0, T))] = 512 if rng.random() < 0.5 else 1024          # the wide-row kernels
+    rows_hi = int(rng.choice([3, 40, 300, 5000, 70000]))
+    rows = [int(rng.integers(1, rows_hi + 1)) for _ in range(T)]
+    B = int(rng.choice([1, 2, 7, 64, 129, 1000, 4096]))
+    pooling = "mean" if rng.random() < 0.5 else "sum"
+    maxL = int(rng.choice([1, 3, 20, 70, 700]))
+    if B * T * maxL > 400000:
+        maxL = max(1, 400000 // (B * T))
+    lens = rng.integers(0, maxL + 1, size=T * B)
+    if rng.random() < 0.3:
+        lens[rng.random(T * B) < 0.5] = 0                                               # many empty bags
+    skew = float(rng.choice([0.0, 1.0, 2.5]))
+    ids = []
+    for t in range(T):
+        n = int(lens[t * B:(t + 1) * B].sum())
+        u = rng.random(n)
+        r = (u ** (1.0 + 3.0 * skew)) * rows[t] if skew > 0 else u * rows[t]            # skew > 0: a hot head
+        ids.append(np.minimum(r.astype(np.int64), rows[t] - 1))
+    ids = np.concatenate(ids) if ids else np.zeros(0, np.int64)
+    io = str(rng.choice(["f32", "f16", "bf16"]))
+    idt = torch.int32 if rng.random() < 0.5 else torch.int64
+    c = float(rng.choice([0.5, 1.0, 3.0]))
+    return dict(dtype=dtype, rows=rows, D=widths, B=B, pooling=pooling, lens=lens, ids=ids, io=io, idt=idt, c=c)
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shape(H, seed):
+    from paper_2508_03854_amd import TBE
+    k = draw_case(seed)
+    cfg = W.Config("rand", list(k["rows"]), list(k["D"]), k["dtype"], k["B"], k["pooling"], ("fixed", 1), ("uniform",))
+    cfg.c, cfg.lr, cfg.eps = k["c"], 0.05, 1e-8
+    off = torch.zeros(len(k["lens"]) + 1, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.as_tensor(k["lens"], dtype=torch.int64), 0)
+    idx = torch.as_tensor(k["ids"], dtype=torch.int64)
+    g = torch.Generator().manual_seed(seed)
+    tabs = H.host_tables(cfg)
+    flat = H.flat_from_tables(tabs)
+    state_np = W.state_rows(cfg, torch.arange(cfg.total_rows)).numpy()
+    state = torch.from_numpy(state_np.copy()).cuda()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, max(1, idx.numel()))
+    for s in range(2):
+        gout = torch.randn(cfg.B, cfg.sum_D, generator=g, dtype=torch.float32)
+        rep = H.check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws, same_inputs=(s == 0),
+                           index_dtype=k["idt"], io=k["io"], ulp_rate=3e-2)   # lr = 0.05: updates as large as the weights
+    print(seed, cfg.T, cfg.B, k["dtype"], k["io"], k["pooling"], idx.numel(), rep, flush=True)
+    tbe.close()
