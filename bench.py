@@ -28,7 +28,8 @@ MEASURED_TRAFFIC_BYTES = {
     # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per launch
     ("C4", "seg_update"): 131.70e9,
     ("C4", "forward_pool"): 40.59e9,
-    ("C4", "seg_long_partial"): 4 * 16.62e9,   # four launches (one per sub-slice sweep) under one timing record
+    ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep) under one timing record
+    ("C4", "seg_dense_partial"): 8.52e9,
 }
 
 
