@@ -178,7 +178,8 @@ def main():
         tbe.timing_enable(True)
         step(args.warmup + args.steps + k)
         for name, ms in tbe.timing_read():
-            d = per_kernel.setdefault(name, {"launches": 0, "ms": 0.0})
+            d = per_kernel.setdefault(name, {"launches": 0, "ms": 0.0, "all": []})
+            d["all"].append(ms)
             d["launches"] += 1
             d["ms"] += ms
     # streaming-copy calibration: achievable bandwidth, and the known-traffic kernel for counter scaling
@@ -209,8 +210,15 @@ def main():
         avg_ms = d["ms"] / d["launches"]
         bytes_per_launch = alg.get(name, 0.0)
         kernels[name] = {"launches_per_step": per_step_launches, "avg_ms": avg_ms, "ms_per_step": d["ms"] / prof_steps,
+                         "min_ms": min(d["all"]), "median_ms": sorted(d["all"])[len(d["all"]) // 2],
                          "alg_bytes_per_launch": bytes_per_launch,
                          "alg_GBps": bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0}
+        measured = None if extended else MEASURED_TRAFFIC_BYTES.get((cfg.name, name))
+        if measured:   # bytes the counters saw per timing record, against what the method must move
+            kernels[name]["measured_bytes"] = measured
+            kernels[name]["measured_GBps"] = measured / (d["ms"] / prof_steps * 1e-3) / 1e9
+            if bytes_per_launch > 0:
+                kernels[name]["amplification"] = measured / (bytes_per_launch * per_step_launches)
     dominant = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dominant]
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -222,6 +230,11 @@ def main():
     step_alg_bytes = sum(alg.get(n, 0.0) * kernels[n]["launches_per_step"] for n in kernels)
     # compulsory bytes of one whole step: the forward set + the backward set (ids are read once more by linearize)
     compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * (8 if args.index_dtype == "i64" else 4)
+
+    wb = 4 if cfg.weight_dtype == "f32" else 2
+    eb = 4 if args.io == "f32" else 2
+    d_bar = cfg.total_elems / max(1, cfg.total_rows)    # row-weighted mean width; ids are spread over rows
+    logical_bytes = (lookups / max(1, args.steps)) * d_bar * (wb + eb)
 
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1): whole tables, full batch size,
     #      as many leading tables as fit the time budget
@@ -279,8 +292,7 @@ def main():
         "value": value, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": (f"{cfg.name}: " if args.rows_scale == 1.0 else f"{cfg.name} with rows x{args.rows_scale}: ")
-                   + W.describe(cfg), "weight_dtype": cfg.weight_dtype, "index_dtype": args.index_dtype,
+        "config": {"workload": ("" if args.rows_scale == 1.0 else f"rows x{args.rows_scale} of ") + W.describe(cfg), "weight_dtype": cfg.weight_dtype, "index_dtype": args.index_dtype,
                    "io_dtype": args.io, "optimizer": args.optimizer,
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
@@ -290,7 +302,13 @@ def main():
         "step_breakdown": {"forward_ms": fwd_ms, "backward_ms": kernel_ms - fwd_ms, "sum_kernel_ms": kernel_ms,
                            "compulsory_bytes_per_step": compulsory,
                            "compulsory_GBps_at_measured_step": compulsory / (ms_per_step * 1e-3) / 1e9,
-                           "all_kernels_alg_bytes_per_step": step_alg_bytes},
+                           "all_kernels_alg_bytes_per_step": step_alg_bytes,
+                           "forward_lookups_per_s": (lookups / max(1, args.steps)) / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
+                           "backward_lookups_per_s": (lookups / max(1, args.steps)) / ((kernel_ms - fwd_ms) * 1e-3)
+                           if kernel_ms > fwd_ms else None,
+                           # cache-level throughput: one table row per lookup (forward) and one gradient slice per
+                           # lookup (backward), whether served by a cache or by HBM; may exceed the HBM peak
+                           "logical_gathered_GBps": logical_bytes / (ms_per_step * 1e-3) / 1e9},
         "measured_copy_GBps": copy_gbps,
         "kernels": kernels,
     }
