@@ -163,7 +163,23 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
         return TBE_EHIP;
     }
     const size_t b_doff = align256(4 * (size_t)(T + 1)), b_rb = align256(8 * (size_t)(T + 1)), b_wo = b_rb;
-    const size_t total = b_doff + b_rb + b_wo + 256;
+    const size_t b_cls = align256(4 * (size_t)T);
+    const size_t total = b_doff + b_rb + b_wo + 256 + b_cls;
+    std::vector<int32_t> cls_tables;
+    {   // forward classes by lanes per row (D / elements per 16-byte fragment, rounded up to a power of two)
+        const int vec = weight_dtype == TBE_F16 ? 8 : 4;
+        std::vector<int32_t> lists[4];
+        for (int t = 0; t < T; ++t) {
+            const int nl = (D[t] + vec - 1) / vec;
+            const int c = nl > 16 ? 0 : (nl > 8 ? 1 : (nl > 4 ? 2 : 3));
+            lists[c].push_back(t);
+        }
+        for (int c = 0; c < 4; ++c) {
+            h->fwd_first[c] = (int)cls_tables.size();
+            h->fwd_count[c] = (int)lists[c].size();
+            cls_tables.insert(cls_tables.end(), lists[c].begin(), lists[c].end());
+        }
+    }
     if (hipMalloc(&h->d_meta, total) != hipSuccess) {
         delete h;
         return TBE_EHIP;
@@ -173,7 +189,9 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     h->d_row_base = reinterpret_cast<int64_t*>(base + b_doff);
     h->d_w_off = reinterpret_cast<int64_t*>(base + b_doff + b_rb);
     h->d_err = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo);
+    h->d_fwd_tables = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo + 256);
     bool ok = hipMemset(h->d_meta, 0, total) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_fwd_tables, cls_tables.data(), 4 * (size_t)T, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_D_off, h->D_off.data(), 4 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_row_base, h->row_base.data(), 8 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_w_off, h->w_off.data(), 8 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;

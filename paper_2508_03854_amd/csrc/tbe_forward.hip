@@ -96,17 +96,20 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
 }
 
 // One kernel per NC so that the common narrow-row case (NC = 1) keeps its register count low enough for
-// 8 wavefronts per SIMD; the host picks the kernel from the widest table of the handle.
+// 8 wavefronts per SIMD; the host picks the kernel from the widest table of the handle.  `tables_of_class` lists
+// the tables this launch covers (those whose rows need more than 16 lanes).
 template <typename WT, int NC, int U, bool MEAN>
 __global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forward_kernel(
     const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
     const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
-    const int32_t B, const int64_t nbags, const int64_t nnz, const int32_t sumD, void* __restrict__ out,
-    const int out_io, int32_t* err) {
-    const int64_t bag = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
-    if (bag >= nbags) return;
-    const int32_t t = (int32_t)(bag / B);
-    const int32_t b = (int32_t)(bag - (int64_t)t * B);
+    const int32_t* __restrict__ tables_of_class, const int32_t n_tables, const int32_t B, const int64_t nnz,
+    const int32_t sumD, void* __restrict__ out, const int out_io, int32_t* err) {
+    const int64_t q = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t i = q / B;
+    if (i >= n_tables) return;
+    const int32_t t = tables_of_class[i];
+    const int32_t b = (int32_t)(q - i * B);
+    const int64_t bag = (int64_t)t * B + b;
     const int32_t d0 = D_off[t];
     const int D = D_off[t + 1] - d0;
     const int64_t R = row_base[t + 1] - row_base[t];
@@ -118,17 +121,125 @@ __global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forw
     forward_bag<WT, NC, U, MEAN>(weights + w_off[t], D, R, indices, start, end, out, out_io, (int64_t)b * sumD + d0, err);
 }
 
+// Narrow rows (at most 16 lanes per row): every lane group of the wavefront takes a bag of its own, G = 64 / LPR
+// consecutive bags of one table per wavefront.  A bag of a dozen narrow rows is a few hundred bytes; with one
+// wavefront per bag the step is bound by the latency of the offsets -> ids -> rows chain, not by bandwidth.
+// A group reads LPR ids with one coalesced load, then walks them U rows at a time.
+template <typename WT, int U, bool MEAN>
+__global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
+    const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
+    const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
+    const int32_t* __restrict__ tables_of_class, const int32_t n_tables, const int lpr_log2, const int32_t B,
+    const int64_t nnz, const int32_t sumD, void* __restrict__ out, const int out_io, int32_t* err) {
+    constexpr int V = RowIO<WT>::kVec;
+    using raw_t = typename RowIO<WT>::raw_t;
+    const int lane = lane_id();
+    const int LPR = 1 << lpr_log2;
+    const int G = kWave >> lpr_log2;
+    const int64_t per_table = ((int64_t)B + G - 1) / G;   // wavefronts per table
+    const int64_t wid = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t i = wid / per_table;
+    if (i >= n_tables) return;
+    const int32_t t = tables_of_class[i];
+    const int sub = lane >> lpr_log2;
+    const int li = lane & (LPR - 1);        // lane inside its group
+    const int lc = li * V;
+    const int64_t b = (wid - i * per_table) * G + sub;
+    const bool has_bag = b < B;
+    const int32_t d0 = D_off[t];
+    const int D = D_off[t + 1] - d0;
+    const int64_t R = row_base[t + 1] - row_base[t];
+    const WT* table = weights + w_off[t];
+    int64_t start = 0, end = 0;
+    if (has_bag) {   // clamped so that a malformed offsets array can never take a read outside indices[0, nnz)
+        const int64_t bag = (int64_t)t * B + b;
+        start = offsets[bag];
+        end = offsets[bag + 1];
+        start = start < 0 ? 0 : (start > nnz ? nnz : start);
+        end = end < start ? start : (end > nnz ? nnz : end);
+    }
+    const int len = (int)((end - start) < (int64_t)0x7FFFFFFF ? (end - start) : (int64_t)0x7FFFFFFF);
+    int maxlen = len;   // longest bag of the wavefront: the loop bounds below are wave-uniform
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int other = __shfl_xor(maxlen, o, kWave);
+        maxlen = other > maxlen ? other : maxlen;
+    }
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    const bool col_on = lc < D;
+    for (int base = 0; base < maxlen; base += LPR) {
+        int32_t my = -1;
+        if (base + li < len) {
+            const int64_t id = indices[start + base + li];
+            if (id >= 0 && id < R) my = (int32_t)id;
+            else atomicOr(err, 1);
+        }
+        const int nk = maxlen - base < LPR ? maxlen - base : LPR;
+        for (int k0 = 0; k0 < nk; k0 += U) {
+            raw_t x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // cross-lane read outside any lane-dependent condition; lanes of a finished bag read -1
+                const int32_t id = __shfl(my, (sub << lpr_log2) + ((k0 + u) & (LPR - 1)), kWave);
+                const bool on = (k0 + u) < nk && id >= 0 && col_on;
+                x[u] = on ? RowIO<WT>::load_raw(table + (int64_t)id * D + lc) : RowIO<WT>::zero_raw();
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) RowIO<WT>::accumulate(x[u], acc);
+        }
+    }
+    float scale = 1.f;
+    if (MEAN) scale = len > 0 ? 1.f / (float)len : 0.f;
+    if (has_bag && col_on) {
+        const int64_t out_elem = b * (int64_t)sumD + d0 + lc;
+#pragma unroll
+        for (int v4 = 0; v4 < V; v4 += 4)
+            store4_from_float(out, out_io, out_elem + v4, acc[v4] * scale, acc[v4 + 1] * scale, acc[v4 + 2] * scale,
+                              acc[v4 + 3] * scale);
+    }
+}
+
 template <typename WT, int NC, int U>
 static void launch_forward_nc(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const IdxView indices,
-                              const IdxView offsets, int32_t B, int64_t nbags, int64_t nnz, bool mean, void* out,
-                              int out_io, dim3 grid, hipStream_t s) {
+                              const IdxView offsets, int32_t B, int64_t nnz, bool mean, void* out, int out_io,
+                              hipStream_t s) {
+    const int n = h->fwd_count[0];
+    if (n == 0) return;
+    const int32_t* list = h->d_fwd_tables + h->fwd_first[0];
+    const int wpb = kFwdThreads / kWave;
+    const dim3 grid((unsigned)(((int64_t)n * B + wpb - 1) / wpb));
     const WT* w = static_cast<const WT*>(tables);
     if (mean)
-        forward_kernel<WT, NC, U, true><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
-                                                                     h->d_row_base, B, nbags, nnz, h->sumD, out, out_io, h->d_err);
+        forward_kernel<WT, NC, U, true><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
+                                                                     list, n, B, nnz, h->sumD, out, out_io, h->d_err);
     else
-        forward_kernel<WT, NC, U, false><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off,
-                                                                      h->d_row_base, B, nbags, nnz, h->sumD, out, out_io, h->d_err);
+        forward_kernel<WT, NC, U, false><<<grid, kFwdThreads, 0, s>>>(w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base,
+                                                                      list, n, B, nnz, h->sumD, out, out_io, h->d_err);
+}
+
+// the narrow-row classes: 16, 8 and 4 lanes per row
+template <typename WT>
+static void launch_forward_groups(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const IdxView indices,
+                                  const IdxView offsets, int32_t B, int64_t nnz, bool mean, void* out, int out_io,
+                                  hipStream_t s) {
+    const WT* w = static_cast<const WT*>(tables);
+    const int wpb = kFwdThreads / kWave;
+    for (int c = 1; c < 4; ++c) {
+        const int n = h->fwd_count[c];
+        if (n == 0) continue;
+        const int lpr_log2 = 5 - c;              // 16, 8, 4 lanes per row
+        const int G = kWave >> lpr_log2;
+        const int64_t waves = (int64_t)n * (((int64_t)B + G - 1) / G);
+        const dim3 grid((unsigned)((waves + wpb - 1) / wpb));
+        const int32_t* list = h->d_fwd_tables + h->fwd_first[c];
+        if (mean)
+            forward_groups_kernel<WT, TBE_FWD_U, true><<<grid, kFwdThreads, 0, s>>>(
+                w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
+        else
+            forward_groups_kernel<WT, TBE_FWD_U, false><<<grid, kFwdThreads, 0, s>>>(
+                w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
+    }
 }
 
 hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const void* indices_p,
@@ -137,17 +248,17 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     const IdxView indices{indices_p, idx32}, offsets{offsets_p, idx32};
     const int64_t nbags = (int64_t)h->T * B;
     if (nbags == 0) return hipSuccess;
-    const int wpb = kFwdThreads / kWave;
-    const dim3 grid((unsigned)((nbags + wpb - 1) / wpb));
     LaunchTimer tm(h, s, "forward_pool");
     const bool mean = pooling == TBE_MEAN;
     if (h->dtype == TBE_F32) {
-        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
-        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
-        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
+        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_groups<float>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     } else {
-        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
-        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nbags, nnz, mean, out, out_io, grid, s);
+        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_groups<__half>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     }
     tm.done();
     return hipGetLastError();

@@ -64,6 +64,12 @@ struct tbe_handle {
     int64_t* d_row_base = nullptr;  // [T+1]
     int64_t* d_w_off = nullptr;     // [T+1]
     int32_t* d_err = nullptr;       // sticky invalid-id flag
+    // Forward classes: 0 = one wavefront per bag; 1..3 = narrow rows (16 / 8 / <=4 lanes per row), where every lane
+    // group of a wavefront takes a bag of its own (4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables
+    // class by class.
+    int32_t* d_fwd_tables = nullptr;  // [T]
+    int fwd_first[4] = {0, 0, 0, 0};
+    int fwd_count[4] = {0, 0, 0, 0};
     // timing
     bool timing = false;
     std::vector<tbe::TimingSlot> slots;  // pool of event pairs
