@@ -168,13 +168,13 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     std::vector<int32_t> cls_tables;
     {   // forward classes by lanes per row (D / elements per 16-byte fragment, rounded up to a power of two)
         const int vec = weight_dtype == TBE_F16 ? 8 : 4;
-        std::vector<int32_t> lists[4];
+        std::vector<int32_t> lists[5];
         for (int t = 0; t < T; ++t) {
             const int nl = (D[t] + vec - 1) / vec;
-            const int c = nl > 16 ? 0 : (nl > 8 ? 1 : (nl > 4 ? 2 : 3));
+            const int c = nl > kFwdGroupMaxLanes ? 0 : (nl > 16 ? 1 : (nl > 8 ? 2 : (nl > 4 ? 3 : 4)));
             lists[c].push_back(t);
         }
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < 5; ++c) {
             h->fwd_first[c] = (int)cls_tables.size();
             h->fwd_count[c] = (int)lists[c].size();
             cls_tables.insert(cls_tables.end(), lists[c].begin(), lists[c].end());

@@ -218,17 +218,17 @@ static void launch_forward_nc(const tbe_handle* h, const void* tables, const int
                                                                       list, n, B, nnz, h->sumD, out, out_io, h->d_err);
 }
 
-// the narrow-row classes: 16, 8 and 4 lanes per row
+// the narrow-row classes: 32, 16, 8 and 4 lanes per row
 template <typename WT>
 static void launch_forward_groups(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const IdxView indices,
                                   const IdxView offsets, int32_t B, int64_t nnz, bool mean, void* out, int out_io,
                                   hipStream_t s) {
     const WT* w = static_cast<const WT*>(tables);
     const int wpb = kFwdThreads / kWave;
-    for (int c = 1; c < 4; ++c) {
+    for (int c = 1; c < 5; ++c) {
         const int n = h->fwd_count[c];
         if (n == 0) continue;
-        const int lpr_log2 = 5 - c;              // 16, 8, 4 lanes per row
+        const int lpr_log2 = 6 - c;              // 32, 16, 8, 4 lanes per row
         const int G = kWave >> lpr_log2;
         const int64_t waves = (int64_t)n * (((int64_t)B + G - 1) / G);
         const dim3 grid((unsigned)((waves + wpb - 1) / wpb));

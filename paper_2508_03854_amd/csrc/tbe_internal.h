@@ -29,6 +29,10 @@ constexpr int kMaxSortSegments = 4096;  // tables beyond this are sorted as one 
 #endif
 constexpr int kDenseRows = TBE_DENSE_ROWS;   // rows per table that the dense-row kernel reduces (multiple of 4)
 constexpr int kDenseChunks = 32;            // bag chunks (= partial sums) per dense row
+#ifndef TBE_FWD_GROUP_MAX_LANES
+#define TBE_FWD_GROUP_MAX_LANES 32
+#endif
+constexpr int kFwdGroupMaxLanes = TBE_FWD_GROUP_MAX_LANES;   // rows of at most this many lanes use one bag per lane group
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
@@ -64,12 +68,12 @@ struct tbe_handle {
     int64_t* d_row_base = nullptr;  // [T+1]
     int64_t* d_w_off = nullptr;     // [T+1]
     int32_t* d_err = nullptr;       // sticky invalid-id flag
-    // Forward classes: 0 = one wavefront per bag; 1..3 = narrow rows (16 / 8 / <=4 lanes per row), where every lane
-    // group of a wavefront takes a bag of its own (4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables
+    // Forward classes: 0 = one wavefront per bag; 1..4 = narrow rows (32 / 16 / 8 / <=4 lanes per row), where every
+    // lane group of a wavefront takes a bag of its own (2 / 4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables
     // class by class.
     int32_t* d_fwd_tables = nullptr;  // [T]
-    int fwd_first[4] = {0, 0, 0, 0};
-    int fwd_count[4] = {0, 0, 0, 0};
+    int fwd_first[5] = {0, 0, 0, 0, 0};
+    int fwd_count[5] = {0, 0, 0, 0, 0};
     // timing
     bool timing = false;
     std::vector<tbe::TimingSlot> slots;  // pool of event pairs
