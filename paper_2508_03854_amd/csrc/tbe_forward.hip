@@ -15,6 +15,9 @@ constexpr int kFwdThreads = 256;
 #ifndef TBE_FWD_U
 #define TBE_FWD_U 4
 #endif
+#ifndef TBE_FWD_GROUP_U
+#define TBE_FWD_GROUP_U 8
+#endif
 #ifndef TBE_FWD_WAVES
 #define TBE_FWD_WAVES 8
 #endif
@@ -234,10 +237,10 @@ static void launch_forward_groups(const tbe_handle* h, const void* tables, const
         const dim3 grid((unsigned)((waves + wpb - 1) / wpb));
         const int32_t* list = h->d_fwd_tables + h->fwd_first[c];
         if (mean)
-            forward_groups_kernel<WT, TBE_FWD_U, true><<<grid, kFwdThreads, 0, s>>>(
+            forward_groups_kernel<WT, TBE_FWD_GROUP_U, true><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
         else
-            forward_groups_kernel<WT, TBE_FWD_U, false><<<grid, kFwdThreads, 0, s>>>(
+            forward_groups_kernel<WT, TBE_FWD_GROUP_U, false><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
     }
 }
