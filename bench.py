@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES = {
     # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per launch
     ("C4", "seg_update"): 131.70e9,
-    ("C4", "forward_pool"): 41.07e9,          # both forward launches (wide and narrow rows) under one timing record
+    ("C4", "forward_pool"): 41.48e9,          # both forward launches (32- and 16-lane rows) under one timing record
     ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep) under one timing record
     ("C4", "seg_dense_partial"): 8.52e9,
 }
