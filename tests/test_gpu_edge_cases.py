@@ -441,3 +441,16 @@ def test_sliced_ticketed_and_dense_paths_are_deterministic():
     seg = dbg["seg_start"].numpy()
     assert np.diff(seg).max() > cfg.B // 8            # some row is long enough for the dense path
     tbe.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_wide_rows_with_bag_sliced_hot_rows(H, dtype):
+    # 1024 columns (the wide-row kernels) and a batch large enough for the bag-sliced hot-row path at that width
+    rng = np.random.default_rng(13)
+    B = 8192                                     # B * 1024 * 4 = 32 MB per table: 64 sub-slices
+    cfg = make_cfg([7, 300], [1024, 520 if dtype == "f16" else 516], dtype=dtype, B=B, pooling="mean", c=2.0)
+    lens = rng.integers(0, 6, size=2 * B)
+    n0, n1 = int(lens[:B].sum()), int(lens[B:].sum())
+    ids = np.concatenate([rng.integers(0, 7, size=n0), rng.integers(0, 300, size=n1)])
+    reps = run_custom(H, cfg, lens, ids)
+    assert reps[0]["max_seg"] > 2000
