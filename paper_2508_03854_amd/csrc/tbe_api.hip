@@ -141,6 +141,7 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
         sumD += D[t];
         h->D_off[t + 1] = (int32_t)sumD;
         if (D[t] > h->maxD) h->maxD = D[t];
+        if (t == 0 || D[t] < h->minD) h->minD = D[t];
         if (h->row_base[t + 1] >= (int64_t)0xFFFFFFFFll || sumD > (int64_t)0x7FFFFFF0ll) {
             delete h;
             return TBE_ESHAPE;
@@ -168,13 +169,13 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     std::vector<int32_t> cls_tables;
     {   // forward classes by lanes per row (D / elements per 16-byte fragment, rounded up to a power of two)
         const int vec = weight_dtype == TBE_F16 ? 8 : 4;
-        std::vector<int32_t> lists[5];
+        std::vector<int32_t> lists[7];
         for (int t = 0; t < T; ++t) {
             const int nl = (D[t] + vec - 1) / vec;
-            const int c = nl > kFwdGroupMaxLanes ? 0 : (nl > 16 ? 1 : (nl > 8 ? 2 : (nl > 4 ? 3 : 4)));
+            const int c = nl > 128 ? 6 : (nl > 64 ? 5 : (nl > kFwdGroupMaxLanes ? 0 : (nl > 16 ? 1 : (nl > 8 ? 2 : (nl > 4 ? 3 : 4)))));
             lists[c].push_back(t);
         }
-        for (int c = 0; c < 5; ++c) {
+        for (int c = 0; c < 7; ++c) {
             h->fwd_first[c] = (int)cls_tables.size();
             h->fwd_count[c] = (int)lists[c].size();
             cls_tables.insert(cls_tables.end(), lists[c].begin(), lists[c].end());

@@ -70,6 +70,7 @@ struct SegArgs {
     const int64_t* row_base;
     const int64_t* w_off;
     int32_t T, B, sumD, maxD;
+    int32_t mixed;         // 1: both row-update kernels run, each on the rows of its own width class
     uint32_t total_rows;
     float lr, eps, inv_c;
     void* tables;
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, 
         a.dense_n[t] = 0u;
     }
     __syncthreads();
-    if (a.seq || slices_for((uint32_t)a.B, D) < 8u) return;
+    if (a.seq || D > 256u || slices_for((uint32_t)a.B, D) < 8u) return;
     const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
     const uint32_t i0 = tbase[t] < nlong ? tbase[t] : nlong, i1 = tbase[t + 1] < nlong ? tbase[t + 1] : nlong;
     const uint32_t thr = (uint32_t)a.B / kDenseDiv > kDenseMin ? (uint32_t)a.B / kDenseDiv : kDenseMin;
@@ -720,14 +721,19 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
             key = a.keys_unique[u];
         }
         const uint32_t len = e - s;
-        const bool live = (u < U) && len >= 1 && len <= (uint32_t)kSegChunk && key < a.total_rows;
+        bool live = (u < U) && len >= 1 && len <= (uint32_t)kSegChunk && key < a.total_rows;
         if ((u < U) && len > (uint32_t)kSegChunk && key < a.total_rows) note_long_row(a, counters, u, key);
         int t = 0, D = 4;
         float v = 0.f;
         if (live) {
             t = table_of_key(a.row_base, a.T, key);
             D = a.D_off[t + 1] - a.D_off[t];
-            v = a.state ? a.state[key] : 0.f;
+            if (D > 256) {   // a wider table's row: the one-wavefront-per-row kernel takes it
+                live = false;
+                D = 4;
+            } else {
+                v = a.state ? a.state[key] : 0.f;
+            }
         }
         int r = 0;
         while (r < (int)rpw) {
@@ -832,11 +838,12 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         const uint32_t key = a.keys_unique[u];
         if (key >= a.total_rows) continue;  // invalid ids: no row
         if (e - s > (uint32_t)kSegChunk) {   // long rows are left to the long-row kernels
-            if (lane_id() == 0) note_long_row(a, counters, u, key);
+            if (lane_id() == 0 && !a.mixed) note_long_row(a, counters, u, key);   // (mixed: already noted)
             continue;
         }
         const int t = table_of_key(a.row_base, a.T, key);
         const int d0 = a.D_off[t];
+        if (a.mixed && a.D_off[t + 1] - d0 <= 256) continue;   // done by the 64-rows-per-wavefront kernel
         const RowGeom g = row_geom(a.D_off[t + 1] - d0);
         WT* wrow = tables + a.w_off[t] + ((int64_t)key - a.row_base[t]) * g.D;
         float acc[4][4];
@@ -917,7 +924,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
 // the two row-update kernels and the hot-row reduction for one gradient element type
 template <typename GT>
 static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* counters, bool mean, bool narrow,
-                               hipStream_t s) {
+                               bool wide, hipStream_t s) {
     const bool f32 = h->dtype == TBE_F32;
     if (narrow) {
         if (f32) {
@@ -927,7 +934,8 @@ static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* 
             if (mean) seg_update_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
             else seg_update_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
         }
-    } else {
+    }
+    if (wide) {
         if (f32) {
             if (mean) seg_update_wide_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
             else seg_update_wide_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
@@ -1023,9 +1031,13 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.cap_chunks = (uint32_t)w.cap_chunks;
     const bool mean = pooling == TBE_MEAN;
     const bool f32 = h->dtype == TBE_F32;
-    const bool narrow = h->maxD <= 256;
-    // the dense-row path: narrow tables only, and only when some table's gradient block is bag-sliced at all
-    const bool dense = narrow && !seq && slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u;
+    // Rows of tables up to 256 columns wide go to the kernel that keeps 64 rows per wavefront, rows of wider tables
+    // to the one-wavefront-per-row kernel; a handle that holds both kinds runs both, each skipping the other's rows.
+    const bool narrow = h->minD <= 256;
+    const bool wide = h->maxD > 256;
+    a.mixed = narrow && wide ? 1 : 0;
+    // the dense-row path: tables up to 256 columns, and only when some such table's gradient block is bag-sliced
+    const bool dense = narrow && !seq && slices_for((uint32_t)B, (uint32_t)(h->maxD < 256 ? h->maxD : 256)) >= 8u;
     uint32_t* tcount = reinterpret_cast<uint32_t*>(ws + w.long_tables);
     uint32_t* tbase = tcount + (h->T + 1);
     uint32_t* tfill = tbase + (h->T + 1);
@@ -1033,9 +1045,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.raw_long = reinterpret_cast<uint2*>(ws + w.raw_long);
     {   // rows with at most kSegChunk lookups; the others are noted for the long-row path
         LaunchTimer tm(h, s, "seg_update");
-        if (grad_io == 0) launch_row_updates<float>(h, a, counters, mean, narrow, s);
-        else if (grad_io == 1) launch_row_updates<__half>(h, a, counters, mean, narrow, s);
-        else launch_row_updates<bf16_t>(h, a, counters, mean, narrow, s);
+        if (grad_io == 0) launch_row_updates<float>(h, a, counters, mean, narrow, wide, s);
+        else if (grad_io == 1) launch_row_updates<__half>(h, a, counters, mean, narrow, wide, s);
+        else launch_row_updates<bf16_t>(h, a, counters, mean, narrow, wide, s);
         tm.done();
     }
     {
@@ -1062,9 +1074,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         uint32_t nsweeps = slices_for((uint32_t)B, (uint32_t)h->maxD) / 8u;
         if (nsweeps < 1u) nsweeps = 1u;
         for (uint32_t sw = 0; sw < nsweeps; ++sw) {
-            if (grad_io == 0) launch_long_partial<float>(a, sw, mean, narrow, s);
-            else if (grad_io == 1) launch_long_partial<__half>(a, sw, mean, narrow, s);
-            else launch_long_partial<bf16_t>(a, sw, mean, narrow, s);
+            if (grad_io == 0) launch_long_partial<float>(a, sw, mean, !wide, s);
+            else if (grad_io == 1) launch_long_partial<__half>(a, sw, mean, !wide, s);
+            else launch_long_partial<bf16_t>(a, sw, mean, !wide, s);
         }
         tm.done();
     }

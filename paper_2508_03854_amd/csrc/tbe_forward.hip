@@ -99,8 +99,8 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
 }
 
 // One kernel per NC so that the common narrow-row case (NC = 1) keeps its register count low enough for
-// 8 wavefronts per SIMD; the host picks the kernel from the widest table of the handle.  `tables_of_class` lists
-// the tables this launch covers (those whose rows need more than 16 lanes).
+// 8 wavefronts per SIMD; the host launches one per width class that has tables.  `tables_of_class` lists the
+// tables this launch covers (those whose rows need more than 64 * (NC / 2) and at most 64 * NC lanes).
 template <typename WT, int NC, int U, bool MEAN>
 __global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forward_kernel(
     const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
@@ -204,12 +204,12 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
 }
 
 template <typename WT, int NC, int U>
-static void launch_forward_nc(const tbe_handle* h, const void* tables, const int32_t* d_D_off, const IdxView indices,
-                              const IdxView offsets, int32_t B, int64_t nnz, bool mean, void* out, int out_io,
-                              hipStream_t s) {
-    const int n = h->fwd_count[0];
+static void launch_forward_nc(const tbe_handle* h, int cls, const void* tables, const int32_t* d_D_off,
+                              const IdxView indices, const IdxView offsets, int32_t B, int64_t nnz, bool mean, void* out,
+                              int out_io, hipStream_t s) {
+    const int n = h->fwd_count[cls];
     if (n == 0) return;
-    const int32_t* list = h->d_fwd_tables + h->fwd_first[0];
+    const int32_t* list = h->d_fwd_tables + h->fwd_first[cls];
     const int wpb = kFwdThreads / kWave;
     const dim3 grid((unsigned)(((int64_t)n * B + wpb - 1) / wpb));
     const WT* w = static_cast<const WT*>(tables);
@@ -254,13 +254,13 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     LaunchTimer tm(h, s, "forward_pool");
     const bool mean = pooling == TBE_MEAN;
     if (h->dtype == TBE_F32) {
-        if (h->maxD <= 256) launch_forward_nc<float, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
-        else if (h->maxD <= 512) launch_forward_nc<float, 2, 4>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
-        else launch_forward_nc<float, 4, 2>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<float, 1, TBE_FWD_U>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<float, 2, 4>(h, 5, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<float, 4, 2>(h, 6, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_groups<float>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     } else {
-        if (h->maxD <= 512) launch_forward_nc<__half, 1, TBE_FWD_U>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
-        else launch_forward_nc<__half, 2, 4>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<__half, 1, TBE_FWD_U>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<__half, 2, 4>(h, 5, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_groups<__half>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     }
     tm.done();

@@ -53,6 +53,7 @@ struct tbe_handle {
     int64_t total_elems = 0;
     int32_t sumD = 0;
     int32_t maxD = 0;
+    int32_t minD = 0;
     int key_bits = 1;  // bits needed to hold the value total_rows (the key given to invalid ids)
     // Sort plan.  Positions arrive grouped by table, so sorting every table's run of positions on its table-local id
     // alone gives the same order as sorting all of them on the linearised key, with fewer key bits whenever
@@ -68,12 +69,12 @@ struct tbe_handle {
     int64_t* d_row_base = nullptr;  // [T+1]
     int64_t* d_w_off = nullptr;     // [T+1]
     int32_t* d_err = nullptr;       // sticky invalid-id flag
-    // Forward classes: 0 = one wavefront per bag; 1..4 = narrow rows (32 / 16 / 8 / <=4 lanes per row), where every
-    // lane group of a wavefront takes a bag of its own (2 / 4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables
-    // class by class.
+    // Forward classes: 0, 5, 6 = one wavefront per bag, rows of at most 64 / 128 / 256 sixteen-byte fragments;
+    // 1..4 = narrow rows (32 / 16 / 8 / <=4 lanes per row), where every lane group of a wavefront takes a bag of its
+    // own (2 / 4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables class by class.
     int32_t* d_fwd_tables = nullptr;  // [T]
-    int fwd_first[5] = {0, 0, 0, 0, 0};
-    int fwd_count[5] = {0, 0, 0, 0, 0};
+    int fwd_first[7] = {0, 0, 0, 0, 0, 0, 0};
+    int fwd_count[7] = {0, 0, 0, 0, 0, 0, 0};
     // timing
     bool timing = false;
     std::vector<tbe::TimingSlot> slots;  // pool of event pairs

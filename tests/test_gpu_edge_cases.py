@@ -454,3 +454,22 @@ def test_wide_rows_with_bag_sliced_hot_rows(H, dtype):
     ids = np.concatenate([rng.integers(0, 7, size=n0), rng.integers(0, 300, size=n1)])
     reps = run_custom(H, cfg, lens, ids)
     assert reps[0]["max_seg"] > 2000
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("pooling", ["sum", "mean"])
+def test_tables_of_every_width_class_in_one_handle(H, dtype, pooling):
+    # One handle with rows of 4 to 1024 columns: every forward class, both row-update kernels (each must take the
+    # rows of its own width class and leave the others alone), hot rows in narrow and in wide tables, and a batch
+    # large enough that the 256-column table's hottest rows take the streamed hot-row path.
+    rng = np.random.default_rng(29)
+    B = 8192
+    v = 8 if dtype == "f16" else 4
+    rows = [5, 400, 9, 1000, 3, 60, 700, 11]
+    D = [1024, 4 * v, 64, 512 + v, 256, 2 * v, 768, 128]
+    cfg = make_cfg(rows, D, dtype=dtype, B=B, pooling=pooling, c=4.0)
+    T = len(rows)
+    lens = rng.integers(0, 6, size=T * B)
+    ids = np.concatenate([rng.integers(0, rows[t], size=int(lens[t * B:(t + 1) * B].sum())) for t in range(T)])
+    reps = run_custom(H, cfg, lens, ids)
+    assert reps[0]["max_seg"] > 4096              # rows of table 4 (256 columns) above the hot-row threshold
