@@ -6,7 +6,7 @@ HBM before the timed region.  Prints ONE JSON line: whole-job lookups/s, the roo
 dominant kernel (duration measured live with HIP events on the launch stream) and the CPU oracle timed on
 a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C1|C3|C4|C5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C1|C3|C4|C5|C5I]
 """
 from __future__ import annotations
 

@@ -105,9 +105,11 @@ def test_full_size_sampled_parity(name):
     assert changed.numel() == U and bool((changed == uq).all()), "set of updated moments differs from unique_rows"
     del changed
 
-    # sampled tables: the changed weight rows are exactly the ids of the batch; all other rows keep their bits
+    # every table: the changed weight rows are exactly the ids of the batch, all other rows keep their bits (the
+    # initial values are re-derived from the generator, so the whole shard is compared without a second copy);
+    # sampled tables: rows checked one by one against the oracle
     tables = sorted({0, T - 1, int(np.argmax(cfg.rows)), int(np.argmin(cfg.rows))} | set(rng.integers(0, T, size=2).tolist()))
-    for t in tables:
+    for t in range(T):
         R, D = cfg.rows[t], cfg.D[t]
         cur = flat[woff[t]:woff[t + 1]].view(R, D)
         moved = torch.zeros(R, dtype=torch.bool, device=dev)
@@ -122,6 +124,8 @@ def test_full_size_sampled_parity(name):
         assert not bool((moved & ~touched).any()), f"table {t}: a row outside the batch changed"
         # (a touched row may keep its bits only if every element's update rounds away; count such rows, expect ~none)
         assert int((touched & ~moved).sum()) <= max(2, touched.sum().item() // 1000), f"table {t}: touched rows unchanged"
+        if t not in tables:
+            continue
 
         # sampled rows: hottest, around the kernel's segment-length classes, singletons
         u_ids, cnt = torch.unique(ids_t, return_counts=True)
@@ -145,7 +149,8 @@ def test_full_size_sampled_parity(name):
                 oa, ob = np.where(a & 0x8000, -(a & 0x7FFF), a), np.where(bb & 0x8000, -(bb & 0x7FFF), bb)
                 assert np.abs(oa - ob).max() <= 1, f"table {t} row {r}: more than one binary16 ulp from the oracle"
             _close(state[rbase[t] + r].item(), v[0], 1e-5, 1e-6, f"table {t} row {r} moment")
-        print("table %d (R=%d, D=%d): update set exact, %d sampled rows ok" % (t, R, D, len(picks)), flush=True)
+        print("table %d (R=%d, D=%d): %d sampled rows ok" % (t, R, D, len(picks)), flush=True)
+    print("all %d tables: the rows that changed are exactly the rows of the batch" % T, flush=True)
     tbe.close()
     del flat, state, state0, idx, off, gout, ws, dbg, ks, vs, uq, ss, cur, moved, touched
     gc.collect()

@@ -38,6 +38,7 @@ def test_c2_full_size(H):
     ("C3", dict(T=12, B=512, rows_scale=2e-3)),       # mixed D in {64,128,256}, hot rows
     ("C4", dict(T=8, B=256, rows_scale=1e-3)),        # fp16 tables, D in {128,256}
     ("C5", dict(T=32, B=1024, rows_scale=1e-3)),      # mean pooling, D=128 and D=32, long-tailed bag lengths
+    ("C5I", dict(T=32, B=1024, rows_scale=1e-3)),     # the same tables, the big ones spread among the small ones
 ])
 def test_scaled_configs(H, name, kw):
     cfg = W.config(name, c=2.0, **kw)

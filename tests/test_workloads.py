@@ -68,3 +68,8 @@ def test_named_configs_have_the_stated_shapes():
     assert c4.T == 256 and abs(c4.total_rows - 4e8) < 1e6 and c4.weight_dtype == "f16" and set(c4.D) == {128, 256}
     assert 170e9 < c4.weight_bytes + 4 * c4.total_rows < 190e9
     assert c5.T == 128 and c5.rows.count(50_000_000) == 8 and c5.rows.count(100_000) == 120 and c5.pooling == "mean"
+    assert c5.rows[:8] == [50_000_000] * 8
+    c5i = W.config("C5I")                       # same tables, the big ones no longer next to one another
+    assert sorted(c5i.rows) == sorted(c5.rows) and sum(c5i.D) == sum(c5.D) and c5i.pooling == "mean"
+    big = [i for i, r in enumerate(c5i.rows) if r == 50_000_000]
+    assert len(big) == 8 and min(np.diff(big)) == 16 and all(c5i.D[i] == 128 for i in big)

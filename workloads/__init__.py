@@ -180,12 +180,17 @@ def config(name: str, *, T: Optional[int] = None, B: Optional[int] = None, rows_
         rows = [max(1000, int(round(r * target / tot))) for r in raw]
         cfg = Config("C4", sc(rows), _choice(seed, 103, t, [128, 256], [0.25, 0.75]), "f16", B or 32768, "sum",
                      ("poisson1", 30.0), ("zipf", 1.1))
-    elif name == "C5":
+    elif name in ("C5", "C5I"):
+        # C5: the big tables first; C5I: the same tables with the big ones spread evenly among the small ones
         t = T or 128
         nbig = max(1, t // 16)
-        rows = [50_000_000] * nbig + [100_000] * (t - nbig)
-        D = [128] * nbig + [32] * (t - nbig)
-        cfg = Config("C5", sc(rows), D, "f32", B or 65536, "mean", ("lognormal", 2.0, 1.0, 500), ("zipf", 1.3))
+        if name == "C5":
+            big = [i < nbig for i in range(t)]
+        else:
+            big = [i % (t // nbig) == (t // nbig) // 2 and i // (t // nbig) < nbig for i in range(t)]
+        rows = [50_000_000 if b else 100_000 for b in big]
+        D = [128 if b else 32 for b in big]
+        cfg = Config(name, sc(rows), D, "f32", B or 65536, "mean", ("lognormal", 2.0, 1.0, 500), ("zipf", 1.3))
     else:
         raise ValueError(f"unknown config {name!r}")
     cfg.seed = seed
