@@ -24,7 +24,7 @@
  *   - The hot calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and return without synchronising.  They are safe to capture into a HIP graph.
  *   - Limits: 4 <= D[t] <= 1024 and D[t] % 4 == 0 (% 8 for fp16 weights); rows[t] < 2^31;
- *     sum(rows) < 2^32 - 1; nnz < 2^32 - 1; T*B < 2^31.
+ *     sum(rows) < 2^32 - 1; nnz <= 2^32 - 2^16; T*B < 2^31.
  *   - Errors are returned as tbe_status; nothing is launched when an argument check fails.  An id
  *     outside its table never causes an out-of-bounds access: the forward skips it, the backward gives
  *     it to no row, and both raise a sticky device flag that tbe_poll_index_error reads back.

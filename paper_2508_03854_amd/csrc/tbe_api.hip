@@ -218,7 +218,8 @@ tbe_status tbe_destroy(tbe_handle* h) {
 
 static tbe_status check_batch(const tbe_handle* h, int32_t B, int64_t nnz) {
     if (B < 1) return TBE_ESHAPE;
-    if (nnz < 0 || nnz >= (int64_t)0xFFFFFFFFll) return TBE_ESHAPE;
+    // positions are 32-bit; the margin keeps every strided position loop (steps of at most one tile) from wrapping
+    if (nnz < 0 || nnz > (int64_t)0xFFFF0000ll) return TBE_ESHAPE;
     if ((int64_t)h->T * B >= ((int64_t)1 << 31)) return TBE_ESHAPE;
     return TBE_OK;
 }
