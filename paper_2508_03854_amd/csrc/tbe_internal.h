@@ -11,7 +11,10 @@
 namespace tbe {
 
 // ---- tunables that fix the workspace layout -------------------------------------------------
-constexpr int kSegChunk = 512;         // a unique row with more lookups than this is split into chunks of this size
+#ifndef TBE_SEG_CHUNK
+#define TBE_SEG_CHUNK 512
+#endif
+constexpr int kSegChunk = TBE_SEG_CHUNK;         // a unique row with more lookups than this is split into chunks of this size
 #ifndef TBE_RADIX_TILE
 #define TBE_RADIX_TILE 4096
 #endif
