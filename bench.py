@@ -11,6 +11,7 @@ a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import math
 import json
 import os
 import sys
@@ -100,6 +101,9 @@ def main():
                     help="element type of out and grad_out (16-bit: *_ex calls)")
     ap.add_argument("--optimizer", choices=["rowwise_adagrad", "sgd"], default="rowwise_adagrad")
     ap.add_argument("--momentum-scale", type=float, default=None, help="override the workload's scaling factor c")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph per pooled batch instead of launching every kernel (small, "
+                         "launch-bound workloads)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -162,9 +166,24 @@ def main():
         step(k)
     torch.cuda.synchronize()
     assert not tbe.poll_index_error()
+    run = step
+    if args.graph:
+        # one graph per distinct (batch, grad_out) pair; the calls record kernels only (no memset, no allocation)
+        side = torch.cuda.Stream()
+        period = pool * n_go // math.gcd(pool, n_go)
+        graphs = []
+        for k in range(period):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step(k)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def run(k):
+            graphs[k % period].replay()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(args.warmup + k)
+        run(args.warmup + k)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     lookups = sum(int(batches[(args.warmup + k) % pool][0].numel()) for k in range(args.steps))
@@ -296,7 +315,8 @@ def main():
                    "io_dtype": args.io, "optimizer": args.optimizer,
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
-                   "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c},
+                   "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c,
+                   "launch": "hip_graph" if args.graph else "eager"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_breakdown": {"forward_ms": fwd_ms, "backward_ms": kernel_ms - fwd_ms, "sum_kernel_ms": kernel_ms,
