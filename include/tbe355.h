@@ -79,7 +79,8 @@ tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D
 
 /* Backward + optimizer, in place (paper Section 2.1: only rows whose ids appear in the batch get a
  * gradient; Section 3.2: a row's gradient is the sum over the samples that hit it; Algorithm 1 steps 5-6).
- * Steps: key[p] = row_base[table of p] + indices[p]; stable ascending radix sort of (key, p);
+ * Steps: key[p] = row_base[table of p] + indices[p]; stable ascending radix sort of the keys (equal keys keep
+ * the order of their positions p);
  * run-length segmentation into unique rows; per unique row u of table t
  *   g      = sum over the row's segment of  s_bag * grad_out[b, D_offsets[t] : D_offsets[t+1]]
  *   v_u    = v_u + ||g||_2^2                       (state, stored unscaled)
@@ -109,6 +110,24 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
                                            int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
                                            float momentum_scale, void* tables, float* state, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
+
+/* The backward in two calls, so that the part that needs only the ids can leave the critical path.
+ * tbe_backward_prepare runs the linearise / sort / run-length steps (Section 2.1: which rows appear in the batch
+ * is known from the ids alone) and leaves their result in `workspace`; it may be enqueued on another stream as soon
+ * as the batch's ids are on the device, concurrently with tbe_forward or with the dense part of the model.
+ * tbe_backward_apply_rowwise_adagrad then does the per-row reduction and the step (Section 3.2, Algorithm 1 steps
+ * 5-6) from grad_out and that workspace.  prepare followed by apply equals tbe_backward_rowwise_adagrad_ex bit for
+ * bit.  The caller orders the two (same stream, or an event), passes the same h, offsets, index_dtype, B, nnz and
+ * workspace to both, leaves the workspace untouched in between, and calls apply exactly once per prepare (apply
+ * consumes counters that prepare cleared).  Argument rules and errors as for the one-call form. */
+tbe_status tbe_backward_prepare(const tbe_handle* h, const void* indices, const void* offsets,
+                                tbe_index_dtype index_dtype, int32_t B, int64_t nnz, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
+tbe_status tbe_backward_apply_rowwise_adagrad(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                              const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz,
+                                              tbe_pooling pooling, float lr, float eps, float momentum_scale,
+                                              void* tables, float* state, void* workspace, size_t workspace_bytes,
+                                              void* hip_stream);
 
 /* Same backward with the plain SGD step the paper names as the conventional alternative to row-wise AdaGrad
  * (Section 3.2, first paragraph):  w_u -= lr * g  once per unique row, g the row's summed gradient as above.

@@ -259,14 +259,19 @@ tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D
     return tbe_forward_ex(h, tables, D_offsets, indices, offsets, TBE_I64, B, nnz, pooling, out, TBE_IO_F32, hip_stream);
 }
 
+// phases of the backward: steps a2-a4 need the ids only, steps a5-a6 need what a2-a4 left in the workspace
+constexpr int kPrepare = 1, kApply = 2;
+
 // shared body of the backward entry points; state == nullptr selects the plain SGD step
 // seq != 0: the non-pooled layout (B is 1, offsets has T+1 entries, grad_out holds grad_elems elements)
 static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* indices,
                                 const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz,
                                 tbe_pooling pooling, float lr, float eps, float momentum_scale, void* tables, float* state,
                                 void* workspace, size_t workspace_bytes, void* hip_stream, int seq = 0,
-                                int64_t grad_elems = 0) {
-    if (!h || !offsets || !tables || ((!indices || !grad_out) && nnz > 0)) return TBE_EINVAL;
+                                int64_t grad_elems = 0, int phases = kPrepare | kApply) {
+    const bool prep = (phases & kPrepare) != 0, apply = (phases & kApply) != 0;
+    if (!h || !offsets || (apply && !tables)) return TBE_EINVAL;
+    if (nnz > 0 && ((prep && !indices) || (apply && !grad_out))) return TBE_EINVAL;
     if (pooling != TBE_SUM && pooling != TBE_MEAN) return TBE_EDTYPE;
     if (!io_ok(grad_dtype) || !idx_ok(index_dtype)) return TBE_EDTYPE;
     if (!isfinite(lr) || !isfinite(eps) || eps < 0.f || !isfinite(momentum_scale) || !(momentum_scale > 0.f))
@@ -284,16 +289,20 @@ static tbe_status backward_impl(const tbe_handle* h, const void* grad_out, tbe_i
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int idx32 = index_dtype == TBE_I32;
-    hipError_t e = launch_linearize(h, indices, offsets, idx32, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
-                                    reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
-    if (e != hipSuccess) return TBE_EHIP;
-    int buf = 0;
-    // pooled: the bag id of every position travels with its key; non-pooled: the position itself
-    e = launch_radix_sort(h, w, ws, nnz, seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos), offsets,
-                          idx32, B, &buf, s);
-    if (e != hipSuccess) return TBE_EHIP;
-    e = launch_run_lengths(h, w, ws, buf, nnz, s);
-    if (e != hipSuccess) return TBE_EHIP;
+    hipError_t e = hipSuccess;
+    int buf = h->sort_passes & 1;  // every pass flips the double buffer, starting from 0
+    if (prep) {
+        e = launch_linearize(h, indices, offsets, idx32, B, nnz, reinterpret_cast<uint32_t*>(ws + w.keys[0]),
+                             reinterpret_cast<uint32_t*>(ws + w.bag_of_pos), s);
+        if (e != hipSuccess) return TBE_EHIP;
+        // pooled: the bag id of every position travels with its key; non-pooled: the position itself
+        e = launch_radix_sort(h, w, ws, nnz, seq ? nullptr : reinterpret_cast<const uint32_t*>(ws + w.bag_of_pos),
+                              offsets, idx32, B, &buf, s);
+        if (e != hipSuccess) return TBE_EHIP;
+        e = launch_run_lengths(h, w, ws, buf, nnz, s);
+        if (e != hipSuccess) return TBE_EHIP;
+    }
+    if (!apply) return TBE_OK;
     e = launch_segment_update(h, w, ws, buf ^ 1, grad_out, (int)grad_dtype, offsets, idx32, B, pooling, lr, eps,
                               momentum_scale, tables, state, seq, grad_elems, s);
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
@@ -307,6 +316,23 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
     if (!state) return TBE_EINVAL;
     return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
                          tables, state, workspace, workspace_bytes, hip_stream);
+}
+
+tbe_status tbe_backward_prepare(const tbe_handle* h, const void* indices, const void* offsets,
+                                tbe_index_dtype index_dtype, int32_t B, int64_t nnz, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+    return backward_impl(h, nullptr, TBE_IO_F32, indices, offsets, index_dtype, B, nnz, TBE_SUM, 0.f, 0.f, 1.f, nullptr,
+                         nullptr, workspace, workspace_bytes, hip_stream, 0, 0, kPrepare);
+}
+
+tbe_status tbe_backward_apply_rowwise_adagrad(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                              const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz,
+                                              tbe_pooling pooling, float lr, float eps, float momentum_scale,
+                                              void* tables, float* state, void* workspace, size_t workspace_bytes,
+                                              void* hip_stream) {
+    if (!state) return TBE_EINVAL;
+    return backward_impl(h, grad_out, grad_dtype, nullptr, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
+                         tables, state, workspace, workspace_bytes, hip_stream, 0, 0, kApply);
 }
 
 tbe_status tbe_lookup_seq(const tbe_handle* h, const void* tables, const void* indices, const void* offsets,

@@ -473,3 +473,53 @@ def test_tables_of_every_width_class_in_one_handle(H, dtype, pooling):
     ids = np.concatenate([rng.integers(0, rows[t], size=int(lens[t * B:(t + 1) * B].sum())) for t in range(T)])
     reps = run_custom(H, cfg, lens, ids)
     assert reps[0]["max_seg"] > 4096              # rows of table 4 (256 columns) above the hot-row threshold
+
+
+@pytest.mark.parametrize("name,kw,idt", [("C3", dict(T=6, B=512, rows_scale=2e-3), torch.int64),
+                                         ("C5", dict(T=16, B=1024, rows_scale=1e-3), torch.int32),
+                                         ("C4", dict(T=4, B=4096, rows_scale=1e-3), torch.int64)])
+def test_prepare_then_apply_equals_the_one_call_backward(name, kw, idt):
+    # the sort of the ids on a second stream, concurrent with the forward, then the row updates on the first one:
+    # bit for bit what the one-call backward gives (which the other tests hold against the oracle)
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    cfg = W.config(name, c=2.0, **kw)
+    idx, off = (x.cuda().to(idt) for x in W.make_batch(cfg, 0))
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, idx.numel())
+    kwargs = dict(pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
+
+    def fresh():
+        flat = torch.empty(cfg.total_elems, dtype=cfg.torch_weight_dtype, device="cuda")
+        W.fill_weights(cfg, flat)
+        state = torch.empty(cfg.total_rows, device="cuda")
+        W.fill_state(cfg, state, "hash")
+        return flat, state
+
+    f1, s1 = fresh()
+    f2, s2 = fresh()
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    out = torch.empty(cfg.B, cfg.sum_D, device="cuda")
+    for step in range(2):
+        gout = W.make_grad_out(cfg, step).cuda()
+        tbe.backward_rowwise_adagrad_ex(gout, idx, off, cfg.B, f1, s1, ws, **kwargs)
+        one = tbe.debug_sorted(ws, cfg.B, idx.numel())
+        side.wait_stream(main)
+        tbe.backward_prepare(idx, off, cfg.B, ws, stream=side)
+        tbe.forward_ex(f2, idx, off, cfg.B, cfg.pooling, out=out)
+        main.wait_stream(side)
+        tbe.backward_apply_rowwise_adagrad(gout, off, cfg.B, idx.numel(), f2, s2, ws, **kwargs)
+        two = tbe.debug_sorted(ws, cfg.B, idx.numel())
+        torch.cuda.synchronize()
+        assert not tbe.poll_index_error()
+        for key in ("keys_sorted", "vals_sorted", "unique_rows", "seg_start"):
+            assert torch.equal(torch.as_tensor(one[key]), torch.as_tensor(two[key])), key
+        assert torch.equal(f1, f2) and torch.equal(s1, s2), f"step {step}: the two-call backward differs"
+    # argument checks of the split calls
+    from paper_2508_03854_amd.binding import TbeError
+    with pytest.raises(TbeError):
+        tbe.backward_prepare(idx, off, cfg.B, ws[:1024])
+    with pytest.raises(TbeError):
+        tbe.backward_apply_rowwise_adagrad(gout, off, cfg.B, idx.numel(), f2, s2, ws[:1024], **kwargs)
+    tbe.close()
