@@ -26,11 +26,21 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
 # known size); see the profile summaries under profiles/.  None = not measured for that workload/kernel.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per launch
+    # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per step under one timing record
+    # (a record with several launches per step carries their sum).  The counters sit behind the L2: they count what the
+    # L2 asked of the fabric, whether the Infinity Cache or HBM served it.
     ("C4", "seg_update"): 131.70e9,
-    ("C4", "forward_pool"): 41.48e9,          # both forward launches (32- and 16-lane rows) under one timing record
-    ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep) under one timing record
+    ("C4", "forward_pool"): 41.48e9,          # both forward launches (32- and 16-lane rows)
+    ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep)
     ("C4", "seg_dense_partial"): 8.52e9,
+    ("C4", "linearize"): 4.39e9,
+    ("C4", "radix_hist"): 3 * 1.12e9,
+    ("C4", "radix_binscan"): 3 * 0.02e9,
+    ("C4", "radix_scatter"): 3 * 4.81e9,
+    ("C4", "rle_count"): 1.06e9,
+    ("C4", "rle_write"): 1.32e9,
+    ("C4", "seg_long_list"): 0.30e9,
+    ("C4", "seg_long_update"): 0.41e9,
 }
 
 
@@ -132,6 +142,8 @@ def main():
     pool = max(1, args.pool)
     batches = W.make_batches(cfg, list(range(pool)), device=dev)
     extended = args.index_dtype != "i64" or args.io != "f32"
+    # the committed counter profiles cover the default call variant of the full-size workload only
+    profiled = not extended and args.rows_scale == 1.0 and args.optimizer == "rowwise_adagrad"
     io_t = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.io]
     if args.index_dtype == "i32":
         batches = [(i.to(torch.int32), o.to(torch.int32)) for i, o in batches]
@@ -232,7 +244,7 @@ def main():
                          "min_ms": min(d["all"]), "median_ms": sorted(d["all"])[len(d["all"]) // 2],
                          "alg_bytes_per_launch": bytes_per_launch,
                          "alg_GBps": bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0}
-        measured = None if extended else MEASURED_TRAFFIC_BYTES.get((cfg.name, name))
+        measured = MEASURED_TRAFFIC_BYTES.get((cfg.name, name)) if profiled else None
         if measured:   # bytes the counters saw per timing record, against what the method must move
             kernels[name]["measured_bytes"] = measured
             kernels[name]["measured_GBps"] = measured / (d["ms"] / prof_steps * 1e-3) / 1e9
@@ -243,13 +255,14 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": dk["alg_GBps"] / HBM_PEAK_GBPS, "avg_launch_ms": dk["avg_ms"],
                 "alg_bytes_per_launch": dk["alg_bytes_per_launch"],
-                "traffic": None if extended else MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant)) if profiled else None}
     fwd_ms = kernels.get("forward_pool", {}).get("ms_per_step", 0.0)
     kernel_ms = sum(k["ms_per_step"] for k in kernels.values())
     step_alg_bytes = sum(alg.get(n, 0.0) * kernels[n]["launches_per_step"] for n in kernels)
     # compulsory bytes of one whole step: the forward set + the backward set (ids are read once more by linearize)
     compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * (8 if args.index_dtype == "i64" else 4)
 
+    counter_bytes = (sum(v for (wl, _), v in MEASURED_TRAFFIC_BYTES.items() if wl == cfg.name) or None) if profiled else None
     wb = 4 if cfg.weight_dtype == "f32" else 2
     eb = 4 if args.io == "f32" else 2
     d_bar = cfg.total_elems / max(1, cfg.total_rows)    # row-weighted mean width; ids are spread over rows
@@ -328,7 +341,14 @@ def main():
                            if kernel_ms > fwd_ms else None,
                            # cache-level throughput: one table row per lookup (forward) and one gradient slice per
                            # lookup (backward), whether served by a cache or by HBM; may exceed the HBM peak
-                           "logical_gathered_GBps": logical_bytes / (ms_per_step * 1e-3) / 1e9},
+                           "logical_gathered_GBps": logical_bytes / (ms_per_step * 1e-3) / 1e9,
+                           # what the byte counters of the profiles saw leave the L2 in one step, over the measured
+                           # step time (null for workloads without a committed counter profile)
+                           "counter_traffic_bytes_per_step": counter_bytes,
+                           "counter_traffic_GBps_at_measured_step":
+                               counter_bytes / (ms_per_step * 1e-3) / 1e9 if counter_bytes else None,
+                           "counter_traffic_frac_of_peak":
+                               counter_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS if counter_bytes else None},
         "measured_copy_GBps": copy_gbps,
         "kernels": kernels,
     }
