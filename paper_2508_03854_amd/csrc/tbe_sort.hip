@@ -21,6 +21,25 @@ __device__ __forceinline__ int64_t upper_bound_i64(const IdxView a, int64_t lo, 
     return lo;
 }
 
+// The same search by a whole wavefront: 64 probes per round cut the range 64-fold, so 8 M offsets take 4 dependent
+// loads instead of 23.  Every lane returns the result.  Terminates for any contents of a (the range shrinks every
+// round) and never reads outside [lo, hi).
+__device__ __forceinline__ int64_t wave_upper_bound_i64(const IdxView a, int64_t lo, int64_t hi, const int64_t x) {
+    const int lane = lane_id();
+    while (lo < hi) {
+        const int64_t step = (hi - lo + kWave - 1) / kWave;
+        const int64_t i = lo + (int64_t)(lane + 1) * step - 1;   // lane's probe; the last lane's is >= hi - 1
+        const bool gt = i < hi ? (a[i] > x) : true;
+        const uint64_t m = __ballot(gt);                         // (a probe beyond hi counts as greater)
+        if (m == 0ull) return hi;                                // all of [lo, hi) is <= x
+        const int f = __ffsll((unsigned long long)m) - 1;        // first probe above x
+        const int64_t i_f = lo + (int64_t)(f + 1) * step - 1;
+        lo += (int64_t)f * step;                                 // the probe before it was <= x
+        hi = i_f < hi ? i_f : hi;
+    }
+    return lo;
+}
+
 // A block owns kLinTile consecutive positions.  It finds the bags that own its first and last position
 // with two binary searches in the global offsets and stages that offsets segment in LDS (relative to the
 // tile start).  Every bag that starts inside the tile then marks its first position, and a running maximum
@@ -40,19 +59,19 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
     const int64_t p0 = (int64_t)blockIdx.x * kLinTile;
     const int64_t p1 = (p0 + kLinTile < N) ? p0 + kLinTile : N;
     if (p0 >= N) return;
-    if (threadIdx.x == 0) {
-        // owner of p: the bag with offsets[bag] <= p < offsets[bag+1]  ==  (first i with offsets[i] > p) - 1.
-        // Searching i in [0, nbags] and clamping keeps every later access in range even for malformed offsets.
-        int64_t lo = upper_bound_i64(offsets, 0, nbags, p0) - 1;
-        int64_t hi = upper_bound_i64(offsets, 0, nbags, p1 - 1) - 1;
-        lo = lo < 0 ? 0 : (lo > nbags - 1 ? nbags - 1 : lo);
-        hi = hi < lo ? lo : (hi > nbags - 1 ? nbags - 1 : hi);
-        s_lo = lo;
-        s_hi = hi;
+    // owner of p: the bag with offsets[bag] <= p < offsets[bag+1]  ==  (first i with offsets[i] > p) - 1.
+    // Searching i in [0, nbags] and clamping keeps every later access in range even for malformed offsets.
+    // Wavefront 0 searches for the tile's first position, wavefront 1 for its last.
+    if ((threadIdx.x >> 6) < 2) {
+        const bool first = (threadIdx.x >> 6) == 0;
+        const int64_t r = wave_upper_bound_i64(offsets, 0, nbags, first ? p0 : p1 - 1) - 1;
+        if ((threadIdx.x & (kWave - 1)) == 0) *(first ? &s_lo : &s_hi) = r;
     }
     for (int i = threadIdx.x; i < kLinTile; i += kLinThreads) s_own[i] = 0;
     __syncthreads();
-    const int64_t lo = s_lo, hi = s_hi;
+    int64_t lo = s_lo, hi = s_hi;
+    lo = lo < 0 ? 0 : (lo > nbags - 1 ? nbags - 1 : lo);
+    hi = hi < lo ? lo : (hi > nbags - 1 ? nbags - 1 : hi);
     const int64_t nb = hi - lo + 1;             // bags touched by this tile (>= 1)
     const bool staged = nb + 1 <= kLinTile + 2;  // nb+1 offsets entries fit in LDS
     if (staged) {
