@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("C4", "forward_pool"): 41.48e9,          # both forward launches (32- and 16-lane rows)
     ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep)
     ("C4", "seg_dense_partial"): 8.52e9,
-    ("C4", "linearize"): 4.39e9,
+    ("C4", "linearize"): 4.48e9,
     ("C4", "radix_hist"): 3 * 1.12e9,
     ("C4", "radix_binscan"): 3 * 0.02e9,
     ("C4", "radix_scatter"): 3 * 4.81e9,
