@@ -155,12 +155,15 @@ struct RowIO<__half> {
     using raw_t = uint4;
     static __device__ __forceinline__ raw_t load_raw(const __half* p) { return *reinterpret_cast<const uint4*>(p); }
     static __device__ __forceinline__ raw_t zero_raw() { return make_uint4(0u, 0u, 0u, 0u); }
+    // acc += float(half): the mixed-precision FMA reads the binary16 operand straight from one half of the 32-bit
+    // register (x * 1.0 + acc, one rounding, the same value as convert-then-add), one instruction instead of two.
+    // The forward is bound by vector-ALU issue at 16-bit rows, so this is its inner loop's main cost.
     static __device__ __forceinline__ void accumulate(const raw_t& r, float (&acc)[8]) {
         const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            acc[2 * i] += __half2float(__ushort_as_half((unsigned short)(w[i] & 0xFFFFu)));
-            acc[2 * i + 1] += __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+            asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]" : "+v"(acc[2 * i]) : "v"(w[i]));
+            asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(acc[2 * i + 1]) : "v"(w[i]));
         }
     }
     static __device__ __forceinline__ void load(const __half* p, float (&x)[8]) {
