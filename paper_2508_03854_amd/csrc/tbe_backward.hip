@@ -39,8 +39,9 @@ __device__ __forceinline__ RowGeom row_geom(int D) {
     const int nl = (D + 3) >> 2;
     g.D = D;
     g.LPR = nl >= kWave ? kWave : pow2ceil64(nl);
-    g.G = kWave / g.LPR;
-    g.sub = lane / g.LPR;
+    const int lpr_log2 = __builtin_ctz((unsigned)g.LPR);   // LPR is a power of two: shifts, not divisions
+    g.G = kWave >> lpr_log2;
+    g.sub = lane >> lpr_log2;
     g.lc = (lane & (g.LPR - 1)) * 4;
     return g;
 }
@@ -737,18 +738,18 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
         }
         int r = 0;
         while (r < (int)rpw) {
-            if (!__shfl((int)live, r, kWave)) {
+            if (!bcast_lane((int)live, r)) {
                 ++r;
                 continue;
             }
-            const RowGeom g = row_geom(__shfl(D, r, kWave));
-            const uint32_t s_r = __shfl(s, r, kWave);
-            const uint32_t len_r = __shfl(len, r, kWave);
+            const RowGeom g = row_geom(bcast_lane(D, r));   // r is the same in all lanes: scalar reads
+            const uint32_t s_r = bcast_lane(s, r);
+            const uint32_t len_r = bcast_lane(len, r);
             if (len_r > (uint32_t)kWave) {
                 // ---- medium row: the whole wavefront reduces it
-                const uint32_t key_r = __shfl(key, r, kWave);
-                const int t_r = __shfl(t, r, kWave);
-                const float v_r = __shfl(v, r, kWave);
+                const uint32_t key_r = bcast_lane(key, r);
+                const int t_r = bcast_lane(t, r);
+                const float v_r = bcast_lane(v, r);
                 float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
                 const GradAddr ga = grad_addr(a, t_r, g.D);
                 segment_reduce<1, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0,
@@ -759,11 +760,59 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                 ++r;
                 continue;
             }
+            if (g.G == 1) {
+                // ---- a short row as wide as the wavefront (more than 128 columns): one row per round, so its
+                // bookkeeping is the same in all lanes and stays on the scalar unit (key, table, bag ids, addresses)
+                const uint32_t key_r = bcast_lane(key, r);
+                const int t_r = bcast_lane(t, r);
+                const float v_r = bcast_lane(v, r);
+                uint32_t my_bag = 0;
+                float my_s = 1.f;
+                if ((uint32_t)lane < len_r) {
+                    my_bag = a.bag_sorted[s_r + lane];
+                    my_s = bag_scale<MEAN>(a.offsets, my_bag);
+                }
+                const bool col_on = g.lc < g.D;
+                const GradAddr ga = grad_addr(a, t_r, g.D);
+                const GT* gcol = static_cast<const GT*>(a.grad_out) + ga.base + g.lc;
+                float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
+                for (uint32_t q0 = 0; q0 < len_r; q0 += kSegUnroll) {
+                    typename GradIO<GT>::raw_t x[kSegUnroll];
+                    float sc[kSegUnroll];
+#pragma unroll
+                    for (int uu = 0; uu < kSegUnroll; ++uu) {
+                        const uint32_t qi = q0 + uu;                                  // < 64 wherever it is used
+                        const uint32_t bag = bcast_lane(my_bag, (int)(qi & (kWave - 1)));
+                        sc[uu] = MEAN ? bcast_lane(my_s, (int)(qi & (kWave - 1))) : 1.f;
+                        const bool on = qi < len_r && col_on;
+                        x[uu] = on ? GradIO<GT>::load(gcol + ((int64_t)bag - ga.row0) * ga.pitch) : GradIO<GT>::zero();
+                    }
+#pragma unroll
+                    for (int uu = 0; uu < kSegUnroll; ++uu) {
+                        const float4 f = GradIO<GT>::to_float(x[uu]);
+                        if (MEAN) {
+                            acc[0][0] = fmaf(sc[uu], f.x, acc[0][0]);
+                            acc[0][1] = fmaf(sc[uu], f.y, acc[0][1]);
+                            acc[0][2] = fmaf(sc[uu], f.z, acc[0][2]);
+                            acc[0][3] = fmaf(sc[uu], f.w, acc[0][3]);
+                        } else {
+                            acc[0][0] += f.x;
+                            acc[0][1] += f.y;
+                            acc[0][2] += f.z;
+                            acc[0][3] += f.w;
+                        }
+                    }
+                }
+                WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
+                adagrad_row<WT, 1>(acc, g, wrow, a.state + key_r, v_r, true, a.lr, a.eps, a.inv_c, a.state == nullptr);
+                ++r;
+                continue;
+            }
             // ---- short rows: rows r .. r+k-1 share the width of row r and have at most 64 lookups in total
             const bool q = live && D == g.D && lane >= r && lane < r + g.G && (e - s_r) <= (uint32_t)kWave;
             const uint64_t m = __ballot(q) >> r;                       // bit j: row r+j qualifies
             const int k = (~m == 0ull) ? kWave : (__ffsll((unsigned long long)(~m)) - 1);  // trailing ones, >= 1
-            const uint32_t tot = __shfl(e, r + k - 1, kWave) - s_r;   // lookups of the k rows, <= 64
+            const uint32_t tot = bcast_lane(e, r + k - 1) - s_r;   // lookups of the k rows, <= 64
             uint32_t my_bag = 0;
             float my_s = 1.f;
             if ((uint32_t)lane < tot) {

@@ -126,6 +126,17 @@ __device__ __forceinline__ void store4_from_float(void* base, int io, int64_t el
 
 // ---- 16-byte row fragments ---------------------------------------------------------------------
 // RowIO<WT>::kVec elements of a table row travel in one 16-byte load.
+// The value a given lane holds, for all lanes, when that lane is the same for the whole wavefront: a scalar read
+// (the result is wavefront-uniform, so what is computed from it stays on the scalar unit) instead of a trip through
+// the LDS crossbar.
+__device__ __forceinline__ int bcast_lane(const int x, const int src) { return __builtin_amdgcn_readlane(x, src); }
+__device__ __forceinline__ uint32_t bcast_lane(const uint32_t x, const int src) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, src);
+}
+__device__ __forceinline__ float bcast_lane(const float x, const int src) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
+}
+
 template <typename WT>
 struct RowIO;
 
