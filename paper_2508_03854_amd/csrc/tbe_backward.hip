@@ -194,7 +194,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
             for (int v = 0; v < 4; ++v) sq = fmaf(acc[c][v], acc[c][v], sq);
         }
     }
-    for (int o = 1; o < g.LPR; o <<= 1) sq += __shfl_xor(sq, o, kWave);  // within the LPR lanes that cover the row
+    sq = group_sum(sq, g.LPR);  // within the LPR lanes that cover the row
     const float v_new = v_old + sq;
     const float denom = sqrtf(v_new * inv_c) + eps;
     const float step = sgd ? lr : (v_new > 0.f ? lr / denom : 0.f);  // v_new == 0 means g == 0: nothing to apply

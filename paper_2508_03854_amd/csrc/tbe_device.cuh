@@ -126,6 +126,25 @@ __device__ __forceinline__ void store4_from_float(void* base, int io, int64_t el
 
 // ---- 16-byte row fragments ---------------------------------------------------------------------
 // RowIO<WT>::kVec elements of a table row travel in one 16-byte load.
+// Sum over the aligned group of LPR lanes (a power of two up to 64) that a lane belongs to, in every lane of the group.
+// Groups of up to 16 lanes lie inside one 16-lane row, where the data-parallel-primitive lane patterns exchange
+// values without a trip through the LDS crossbar: neighbours, pairs of a quad, the mirrored half row, the mirrored
+// row; only the steps across rows (16, 32) take the general shuffle.  All 64 lanes must be active.  The order of the
+// additions is fixed, so the result does not depend on timing.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(const float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float group_sum(float x, const int LPR) {
+    if (LPR >= 2) x += dpp_lane<0xB1>(x);     // quad_perm [1,0,3,2]
+    if (LPR >= 4) x += dpp_lane<0x4E>(x);     // quad_perm [2,3,0,1]
+    if (LPR >= 8) x += dpp_lane<0x141>(x);    // row_half_mirror: lane i <- lane 7-i of its half row
+    if (LPR >= 16) x += dpp_lane<0x140>(x);   // row_mirror: lane i <- lane 15-i of its row
+    if (LPR >= 32) x += __shfl_xor(x, 16, 64);
+    if (LPR >= 64) x += __shfl_xor(x, 32, 64);
+    return x;
+}
+
 // The value a given lane holds, for all lanes, when that lane is the same for the whole wavefront: a scalar read
 // (the result is wavefront-uniform, so what is computed from it stays on the scalar unit) instead of a trip through
 // the LDS crossbar.
