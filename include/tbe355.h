@@ -136,6 +136,12 @@ tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dt
                             const void* offsets, tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling,
                             float lr, void* tables, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The plain SGD step on a workspace that tbe_backward_prepare filled: prepare + this call equal tbe_backward_sgd bit
+ * for bit (Section 3.2, first paragraph, for the step; rules as for tbe_backward_apply_rowwise_adagrad). */
+tbe_status tbe_backward_apply_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* offsets,
+                                  tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
+                                  void* tables, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Non-pooled lookup and its backward (Section 2.1: the forward maps categorical ids to embedding rows; this is
  * that map without pooling, as needed by features that are a long sequence of event ids per sample).
  *   offsets  DEVICE [T+1], ascending from 0 to nnz: the ids of table t are indices[offsets[t] .. offsets[t+1])

@@ -24,7 +24,7 @@ _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
            "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_prepare",
-           "tbe_backward_apply_rowwise_adagrad", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
+           "tbe_backward_apply_rowwise_adagrad", "tbe_backward_apply_sgd", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
            "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable",
            "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_status_string"]
 
@@ -72,6 +72,9 @@ def load_library():
     L.tbe_backward_apply_rowwise_adagrad.restype = ctypes.c_int
     L.tbe_backward_apply_rowwise_adagrad.argtypes = [vp, vp, ctypes.c_int, vp, ctypes.c_int, i32, i64, ctypes.c_int,
                                                      f32, f32, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    L.tbe_backward_apply_sgd.restype = ctypes.c_int
+    L.tbe_backward_apply_sgd.argtypes = [vp, vp, ctypes.c_int, vp, ctypes.c_int, i32, i64, ctypes.c_int, f32, vp, vp,
+                                         ctypes.c_size_t, vp]
     L.tbe_backward_sgd.restype = ctypes.c_int
     L.tbe_backward_sgd.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int, f32, vp, vp,
                                    ctypes.c_size_t, vp]
@@ -272,6 +275,25 @@ class TBE:
             _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(state, torch.float32, "state"),
             _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
         _check(st, "tbe_backward_apply_rowwise_adagrad")
+
+    def backward_apply_sgd(self, grad_out: torch.Tensor, offsets: torch.Tensor, B: int, nnz: int, tables: torch.Tensor,
+                           workspace: torch.Tensor, *, pooling: str = "sum", lr: float,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Row gradients and the plain SGD step from a workspace that backward_prepare filled for the same batch."""
+        if tables.numel() != self.total_elems:
+            raise ValueError("tables shape does not match the handle")
+        if grad_out.shape != (B, self.sum_D) or offsets.numel() != self.T * B + 1:
+            raise ValueError("grad_out / offsets shape does not match the handle")
+        if grad_out.dtype not in _IO:
+            raise TypeError(f"grad_out must be float32, float16 or bfloat16, got {grad_out.dtype}")
+        if offsets.dtype not in _IDX:
+            raise TypeError(f"offsets must be int64 or int32, got {offsets.dtype}")
+        st = self._lib.tbe_backward_apply_sgd(
+            self._h, _dev_ptr(grad_out, grad_out.dtype, "grad_out"), _IO[grad_out.dtype],
+            _dev_ptr(offsets, offsets.dtype, "offsets"), _IDX[offsets.dtype], int(B), int(nnz),
+            {"sum": SUM, "mean": MEAN}[pooling], float(lr), _dev_ptr(tables, self.torch_dtype, "tables"),
+            _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
+        _check(st, "tbe_backward_apply_sgd")
 
     # ---- tbe_backward_sgd
     def backward_sgd(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor, B: int,

@@ -366,6 +366,13 @@ tbe_status tbe_backward_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dt
                          nullptr, workspace, workspace_bytes, hip_stream);
 }
 
+tbe_status tbe_backward_apply_sgd(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype, const void* offsets,
+                                  tbe_index_dtype index_dtype, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
+                                  void* tables, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return backward_impl(h, grad_out, grad_dtype, nullptr, offsets, index_dtype, B, nnz, pooling, lr, 0.f, 1.f, tables,
+                         nullptr, workspace, workspace_bytes, hip_stream, 0, 0, kApply);
+}
+
 tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,
                                         const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float lr,
                                         float eps, float momentum_scale, void* tables, float* state, void* workspace,

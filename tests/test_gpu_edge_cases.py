@@ -516,6 +516,14 @@ def test_prepare_then_apply_equals_the_one_call_backward(name, kw, idt):
         for key in ("keys_sorted", "vals_sorted", "unique_rows", "seg_start"):
             assert torch.equal(torch.as_tensor(one[key]), torch.as_tensor(two[key])), key
         assert torch.equal(f1, f2) and torch.equal(s1, s2), f"step {step}: the two-call backward differs"
+    # the same for the plain SGD step
+    g1, g2 = f1.clone(), f1.clone()
+    gout = W.make_grad_out(cfg, 7).cuda()
+    tbe.backward_sgd(gout, idx, off, cfg.B, g1, ws, pooling=cfg.pooling, lr=cfg.lr)
+    tbe.backward_prepare(idx, off, cfg.B, ws)
+    tbe.backward_apply_sgd(gout, off, cfg.B, idx.numel(), g2, ws, pooling=cfg.pooling, lr=cfg.lr)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2) and not torch.equal(g1, f1)
     # argument checks of the split calls
     from paper_2508_03854_amd.binding import TbeError
     with pytest.raises(TbeError):
