@@ -219,7 +219,7 @@ __global__ __launch_bounds__(1024) void radix_plan_kernel(const IdxView offsets,
 __device__ __forceinline__ void hist_add(uint32_t* __restrict__ hw, const uint32_t d, const bool valid) {
     const uint64_t act = __ballot(valid);
     if (act == 0ull) return;
-    const uint32_t d0 = __shfl(d, __ffsll((unsigned long long)act) - 1, kWave);
+    const uint32_t d0 = bcast_lane(d, __ffsll((unsigned long long)act) - 1);   // (the first active lane's digit)
     const uint64_t same = __ballot(valid && d == d0);
     if (same == act) {
         if (lane_id() == __ffsll((unsigned long long)act) - 1) atomicAdd(&hw[d0], (uint32_t)__popcll(act));
