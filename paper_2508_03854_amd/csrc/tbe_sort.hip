@@ -306,6 +306,103 @@ __global__ __launch_bounds__(kRsThreads) void radix_binscan_kernel(uint32_t* __r
     for (int i = threadIdx.x; i < nchunks; i += kRsThreads) row[i] -= s_b0[pl.desc[i].z];
 }
 
+// One tile of a chunk.  FULL: all kRadixTile positions exist, so nothing is predicated (all but a chunk's last tile).
+template <bool FULL>
+__device__ __forceinline__ uint32_t scatter_tile(
+    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, uint32_t* __restrict__ keys_out,
+    uint32_t* __restrict__ vals_out, const int64_t tile, const int64_t e, const int shift, const uint32_t mask,
+    const bool iota_vals, const int globalize, const int64_t* __restrict__ row_base, const int32_t B,
+    const uint32_t invalid_key, const int seg, uint32_t (*s_cnt)[kRsBins], uint32_t* s_base, uint32_t* s_dstart,
+    uint32_t* s_keys, uint32_t* s_vals, uint32_t* s_scan) {
+    const int tid = threadIdx.x;
+    const int lane = lane_id();
+    const int w = tid >> 6;
+    const uint64_t lt = lanemask_lt();
+    for (int i = tid; i < kRsWaves * kRsBins; i += kRsThreads) (&s_cnt[0][0])[i] = 0u;
+    __syncthreads();  // also orders the s_base update / s_keys reads of the previous tile
+
+    uint32_t key[kRsItems], val[kRsItems], off[kRsItems];
+    const int64_t wbase = tile + (int64_t)w * (kWave * kRsItems);
+#pragma unroll
+    for (int k = 0; k < kRsItems; ++k) {
+        const int64_t i = wbase + k * kWave + lane;
+        const bool valid = FULL || i < e;
+        key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
+        val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // iota: the payload is the position itself
+    }
+    // Rank inside the wave, item by item in input order.  peers = the valid lanes that hold the same digit: per digit
+    // bit one ballot, and the lanes that agree with this lane's bit are  ~(ballot ^ (all ones if the bit is set)).
+#pragma unroll
+    for (int k = 0; k < kRsItems; ++k) {
+        const int64_t i = wbase + k * kWave + lane;
+        const bool valid = FULL || i < e;
+        const uint32_t d = (key[k] >> shift) & mask;
+        const uint64_t vmask = FULL ? ~0ull : __builtin_amdgcn_ballot_w64(valid);
+        uint32_t plo = (uint32_t)vmask, phi = (uint32_t)(vmask >> 32);
+        const uint32_t dv = (FULL || valid) ? d : 0u;   // lanes without an element vote in no ballot
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {   // (bits above the digit's width are zero in every lane: those rounds change nothing)
+            const uint64_t m = __builtin_amdgcn_uicmp(dv & (1u << b), 0u, 33 /* != */);   // lanes whose digit has bit b
+            const uint32_t sel = (uint32_t)__builtin_amdgcn_sbfe((int)d, b, 1);           // all ones if this lane's has
+            plo &= ~((uint32_t)m ^ sel);
+            phi &= ~((uint32_t)(m >> 32) ^ sel);
+        }
+        const uint64_t peers = ((uint64_t)phi << 32) | plo;   // never empty for a valid lane: it holds the lane itself
+        uint32_t old = 0;
+        const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : 0;
+        if (valid && lane == leader) old = atomicAdd(&s_cnt[w][d], (uint32_t)__popcll(peers));
+        old = __shfl(old, leader, kWave);
+        off[k] = old + (uint32_t)__popcll(peers & lt);
+    }
+    __syncthreads();
+    // per digit: exclusive offsets over the waves, tile total, exclusive scan over the digits
+    uint32_t my_tot = 0;
+    {
+        uint32_t run = 0;
+#pragma unroll
+        for (int ww = 0; ww < kRsWaves; ++ww) {
+            const uint32_t c = s_cnt[ww][tid];
+            s_cnt[ww][tid] = run;
+            run += c;
+        }
+        my_tot = run;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<kRsThreads>(my_tot, s_scan, &tot);
+        s_dstart[tid] = ex;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kRsItems; ++k) {
+        const int64_t i = wbase + k * kWave + lane;
+        if (FULL || i < e) {
+            const uint32_t d = (key[k] >> shift) & mask;
+            const uint32_t pos = s_dstart[d] + s_cnt[w][d] + off[k];
+            s_keys[pos] = key[k];
+            s_vals[pos] = val[k];
+        }
+    }
+    __syncthreads();
+    const int cnt = FULL ? kRadixTile : (int)(e - tile);
+    for (int j = tid; j < cnt; j += kRsThreads) {
+        const uint32_t kk = s_keys[j];
+        const uint32_t d = (kk >> shift) & mask;
+        const uint32_t dst = s_base[d] + ((uint32_t)j - s_dstart[d]);
+        const uint32_t vv = s_vals[j];
+        uint32_t ko = kk;
+        if (globalize) {   // last pass of a segmented sort: table-local id -> linearised row key
+            // the table comes from the lookup's bag where the payload is one (so that key and bag always agree),
+            // else from the segment
+            const int t = globalize == 1 ? (int)(vv / (uint32_t)B) : seg;
+            const int64_t rb = row_base[t];
+            ko = ((int64_t)kk >= row_base[t + 1] - rb) ? invalid_key : (uint32_t)(rb + kk);
+        }
+        keys_out[dst] = ko;
+        vals_out[dst] = vv;
+    }
+    __syncthreads();
+    return my_tot;
+}
+
 __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in,
                                                                    const uint32_t* __restrict__ vals_in,
                                                                    uint32_t* __restrict__ keys_out,
@@ -324,10 +421,6 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
     __shared__ uint32_t s_scan[kRsWaves];
 
     const int tid = threadIdx.x;
-    const int lane = lane_id();
-    const int w = tid >> 6;
-    const uint64_t lt = lanemask_lt();
-
     if (blockIdx.x >= pl.chunk0[pl.nseg]) return;
     const uint4 ds = pl.desc[blockIdx.x];
     const int64_t s = ds.x, e = ds.y;
@@ -339,85 +432,14 @@ __global__ __launch_bounds__(kRsThreads) void radix_scatter_kernel(const uint32_
         const uint32_t ex = block_excl_scan<kRsThreads>(t, s_scan, &tot);
         s_base[tid] = (tid < nbins) ? pl.bounds[seg] + ex + ghist[(size_t)tid * pl.G + blockIdx.x] : 0u;
     }
-
     for (int64_t tile = s; tile < e; tile += kRadixTile) {
-        for (int i = tid; i < kRsWaves * kRsBins; i += kRsThreads) (&s_cnt[0][0])[i] = 0u;
-        __syncthreads();  // also orders the s_base update / s_keys reads of the previous tile
-
-        uint32_t key[kRsItems], val[kRsItems], off[kRsItems];
-        const int64_t wbase = tile + (int64_t)w * (kWave * kRsItems);
-#pragma unroll
-        for (int k = 0; k < kRsItems; ++k) {
-            const int64_t i = wbase + k * kWave + lane;
-            const bool valid = i < e;
-            key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
-            val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // iota: the payload is the position itself
-        }
-        // rank inside the wave, item by item in input order: peers = valid lanes holding the same digit
-#pragma unroll
-        for (int k = 0; k < kRsItems; ++k) {
-            const int64_t i = wbase + k * kWave + lane;
-            const bool valid = i < e;
-            const uint32_t d = (key[k] >> shift) & mask;
-            uint64_t peers = __ballot(valid);
-#pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const bool bit = (d >> b) & 1u;
-                const uint64_t m = __ballot(valid && bit);
-                peers &= bit ? m : ~m;
-            }
-            uint32_t old = 0;
-            const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : 0;
-            if (valid && lane == leader) old = atomicAdd(&s_cnt[w][d], (uint32_t)__popcll(peers));
-            old = __shfl(old, leader, kWave);
-            off[k] = old + (uint32_t)__popcll(peers & lt);
-        }
-        __syncthreads();
-        // per digit: exclusive offsets over the waves, tile total, exclusive scan over the digits
-        uint32_t my_tot = 0;
-        {
-            uint32_t run = 0;
-#pragma unroll
-            for (int ww = 0; ww < kRsWaves; ++ww) {
-                const uint32_t c = s_cnt[ww][tid];
-                s_cnt[ww][tid] = run;
-                run += c;
-            }
-            my_tot = run;
-            uint32_t tot;
-            const uint32_t ex = block_excl_scan<kRsThreads>(my_tot, s_scan, &tot);
-            s_dstart[tid] = ex;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < kRsItems; ++k) {
-            const int64_t i = wbase + k * kWave + lane;
-            if (i < e) {
-                const uint32_t d = (key[k] >> shift) & mask;
-                const uint32_t pos = s_dstart[d] + s_cnt[w][d] + off[k];
-                s_keys[pos] = key[k];
-                s_vals[pos] = val[k];
-            }
-        }
-        __syncthreads();
-        const int cnt = (int)((e - tile) < (int64_t)kRadixTile ? (e - tile) : (int64_t)kRadixTile);
-        for (int j = tid; j < cnt; j += kRsThreads) {
-            const uint32_t kk = s_keys[j];
-            const uint32_t d = (kk >> shift) & mask;
-            const uint32_t dst = s_base[d] + ((uint32_t)j - s_dstart[d]);
-            const uint32_t vv = s_vals[j];
-            uint32_t ko = kk;
-            if (globalize) {   // last pass of a segmented sort: table-local id -> linearised row key
-                // the table comes from the lookup's bag where the payload is one (so that key and bag always agree),
-                // else from the segment
-                const int t = globalize == 1 ? (int)(vv / (uint32_t)B) : seg;
-                const int64_t rb = row_base[t];
-                ko = ((int64_t)kk >= row_base[t + 1] - rb) ? invalid_key : (uint32_t)(rb + kk);
-            }
-            keys_out[dst] = ko;
-            vals_out[dst] = vv;
-        }
-        __syncthreads();
+        uint32_t my_tot;
+        if (e - tile >= (int64_t)kRadixTile)
+            my_tot = scatter_tile<true>(keys_in, vals_in, keys_out, vals_out, tile, e, shift, mask, iota_vals,
+                                        globalize, row_base, B, invalid_key, seg, s_cnt, s_base, s_dstart, s_keys, s_vals, s_scan);
+        else
+            my_tot = scatter_tile<false>(keys_in, vals_in, keys_out, vals_out, tile, e, shift, mask, iota_vals,
+                                         globalize, row_base, B, invalid_key, seg, s_cnt, s_base, s_dstart, s_keys, s_vals, s_scan);
         s_base[tid] += my_tot;
     }
 }
