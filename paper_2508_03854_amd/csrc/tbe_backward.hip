@@ -910,6 +910,9 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
 // ---- 4. one workgroup per long row: add its partial sums, then the step ----------------------------------
 // Wavefront w adds slots w, w+4, ... in ascending order, the four sums are added in wavefront order, and
 // wavefront 0 applies the step: a fixed order, so the result does not depend on scheduling.
+#ifndef TBE_LONG_UPDATE_BLOCKS
+#define TBE_LONG_UPDATE_BLOCKS 2048
+#endif
 template <typename WT>
 __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegArgs a) {
     __shared__ float s_sum[kSegThreads / kWave][1024];
@@ -1131,8 +1134,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     }
     {
         LaunchTimer tm(h, s, "seg_long_update");
-        if (f32) seg_long_update_kernel<float><<<512, kSegThreads, 0, s>>>(a);
-        else seg_long_update_kernel<__half><<<512, kSegThreads, 0, s>>>(a);
+        // one row per workgroup and round, a dependent chain of loads each: enough workgroups to fill every CU's slots
+        if (f32) seg_long_update_kernel<float><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<__half><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
         tm.done();
     }
     return hipGetLastError();

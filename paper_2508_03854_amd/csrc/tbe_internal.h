@@ -23,7 +23,10 @@ constexpr int kRadixTile = TBE_RADIX_TILE;  // elements per radix-sort tile (256
 #define TBE_RADIX_MAX_BLOCKS 8192
 #endif
 constexpr int kRadixMaxBlocks = TBE_RADIX_MAX_BLOCKS;  // each radix block owns one contiguous slice of the input
-constexpr int kRleTile = 2048;         // elements per run-length tile
+#ifndef TBE_RLE_TILE
+#define TBE_RLE_TILE 2048
+#endif
+constexpr int kRleTile = TBE_RLE_TILE;  // elements per run-length tile (at most 4096: one wavefront scans its runs of 64)
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
 constexpr int kMaxSortSegments = 4096;  // tables beyond this are sorted as one segment on the linearised key

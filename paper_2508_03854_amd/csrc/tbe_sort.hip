@@ -506,7 +506,8 @@ hipError_t launch_radix_sort(const tbe_handle* h, const Workspace& w, char* ws, 
 // =================================================================================================
 constexpr int kRleThreads = 256;
 constexpr int kRleItems = kRleTile / kRleThreads;            // 8
-constexpr int kRleRuns = kRleItems * (kRleThreads / kWave);  // 32 runs of 64 elements
+constexpr int kRleRuns = kRleItems * (kRleThreads / kWave);  // runs of 64 elements per tile
+static_assert(kRleRuns <= kWave, "one wavefront scans the run counts of a tile");
 
 __device__ __forceinline__ bool is_head(const uint32_t* __restrict__ keys, int64_t i, int64_t N) {
     if (i >= N) return false;
