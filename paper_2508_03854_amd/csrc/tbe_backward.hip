@@ -1105,10 +1105,10 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     {
         LaunchTimer tm(h, s, "seg_long_list");
         seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
-        seg_long_fill_kernel<<<64, 256, 0, s>>>(a, counters, tbase, tfill);
+        seg_long_fill_kernel<<<512, 256, 0, s>>>(a, counters, tbase, tfill);
         if (dense) seg_dense_select_kernel<<<h->T, 256, 0, s>>>(a, tbase);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
-        if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<256, kSegThreads, 0, s>>>(a);
+        if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<2048, kSegThreads, 0, s>>>(a);   // (a chain of ~17 dependent loads per row: many waves)
         if (dense) seg_dense_bounds_kernel<<<h->T, kSegThreads, 0, s>>>(a);
         tm.done();
     }

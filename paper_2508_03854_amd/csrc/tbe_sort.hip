@@ -536,12 +536,18 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
     for (int i = threadIdx.x; i < zero_words; i += 1024) zero[i] = 0u;  // per-table long-row counters, unit tickets
     __shared__ uint32_t smem[1024 / kWave];
     uint32_t carry = 0;
-    for (int base = 0; base < nblocks; base += 1024) {
-        const int i = base + threadIdx.x;
-        const uint32_t v = (i < nblocks) ? block_counts[i] : 0u;
+    for (int base = 0; base < nblocks; base += 4 * 1024) {   // four counts per thread and round: a quarter of the barriers
+        const int i = base + 4 * (int)threadIdx.x;
+        uint32_t v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = (i + q < nblocks) ? block_counts[i + q] : 0u;
         uint32_t tot;
-        const uint32_t ex = block_excl_scan<1024>(v, smem, &tot);
-        if (i < nblocks) block_counts[i] = carry + ex;
+        uint32_t run = carry + block_excl_scan<1024>(v[0] + v[1] + v[2] + v[3], smem, &tot);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i + q < nblocks) block_counts[i + q] = run;
+            run += v[q];
+        }
         carry += tot;
     }
     if (threadIdx.x == 0) {
