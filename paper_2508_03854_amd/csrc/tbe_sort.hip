@@ -288,12 +288,18 @@ __global__ __launch_bounds__(kRsThreads) void radix_binscan_kernel(uint32_t* __r
     uint32_t* row = ghist + (size_t)blockIdx.x * pl.G;
     const int nchunks = (int)pl.chunk0[pl.nseg];   // < G; row[nchunks] is an unused column holding zero
     uint32_t carry = 0;
-    for (int base = 0; base <= nchunks; base += kRsThreads) {
-        const int i = base + threadIdx.x;
-        const uint32_t v = (i <= nchunks) ? row[i] : 0u;
+    for (int base = 0; base <= nchunks; base += 4 * kRsThreads) {   // four counts per thread and round
+        const int i = base + 4 * (int)threadIdx.x;
+        uint32_t v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = (i + q <= nchunks) ? row[i + q] : 0u;
         uint32_t tot;
-        const uint32_t ex = block_excl_scan<kRsThreads>(v, smem, &tot);
-        if (i <= nchunks) row[i] = carry + ex;     // row[nchunks] = total
+        uint32_t run = carry + block_excl_scan<kRsThreads>(v[0] + v[1] + v[2] + v[3], smem, &tot);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i + q <= nchunks) row[i + q] = run;     // row[nchunks] = total
+            run += v[q];
+        }
         carry += tot;
     }
     __syncthreads();
