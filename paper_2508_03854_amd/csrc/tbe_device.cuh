@@ -145,6 +145,23 @@ __device__ __forceinline__ float group_sum(float x, const int LPR) {
     return x;
 }
 
+// Maximum over the wavefront, as a wavefront-uniform value: inside the 16-lane rows by DPP lane patterns, across
+// the four rows by scalar lane reads.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ int dpp_lane_i32(const int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ int wave_max_i32(int x) {
+    int o = dpp_lane_i32<0xB1>(x);  x = o > x ? o : x;    // quad_perm [1,0,3,2]
+    o = dpp_lane_i32<0x4E>(x);      x = o > x ? o : x;    // quad_perm [2,3,0,1]
+    o = dpp_lane_i32<0x141>(x);     x = o > x ? o : x;    // row_half_mirror
+    o = dpp_lane_i32<0x140>(x);     x = o > x ? o : x;    // row_mirror: every lane holds its row's maximum
+    const int a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
+    const int c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
+    const int ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
 // The value a given lane holds, for all lanes, when that lane is the same for the whole wavefront: a scalar read
 // (the result is wavefront-uniform, so what is computed from it stays on the scalar unit) instead of a trip through
 // the LDS crossbar.

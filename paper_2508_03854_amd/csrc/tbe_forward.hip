@@ -162,11 +162,7 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
         end = end < start ? start : (end > nnz ? nnz : end);
     }
     const int len = (int)((end - start) < (int64_t)0x7FFFFFFF ? (end - start) : (int64_t)0x7FFFFFFF);
-    int maxlen = len;   // longest bag of the wavefront: the loop bounds below are wave-uniform
-    for (int o = 1; o < kWave; o <<= 1) {
-        const int other = __shfl_xor(maxlen, o, kWave);
-        maxlen = other > maxlen ? other : maxlen;
-    }
+    const int maxlen = wave_max_i32(len);   // longest bag of the wavefront: the loop bounds below are wave-uniform
     float acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.f;
