@@ -172,7 +172,11 @@ __device__ __forceinline__ void fold_groups(float (&acc)[NC][4], const RowGeom& 
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[c][v] += __shfl_xor(acc[c][v], o, kWave);
+            for (int v = 0; v < 4; ++v) {
+                if (o == 32) acc[c][v] = pair_sum<32>(acc[c][v]);        // the two halves / odd and even rows: in place
+                else if (o == 16) acc[c][v] = pair_sum<16>(acc[c][v]);
+                else acc[c][v] += __shfl_xor(acc[c][v], o, kWave);
+            }
     }
 }
 

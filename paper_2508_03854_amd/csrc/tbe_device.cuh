@@ -135,13 +135,27 @@ template <int CTRL>
 __device__ __forceinline__ float dpp_lane(const float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
 }
+// x[lane] + x[lane ^ O] for O = 16 or 32, the same bits in both partners: the gfx950 row-swap instructions exchange
+// the odd and even 16-lane rows (or the two 32-lane halves) of two registers in place, again without the LDS crossbar
+// (lane layout checked on the device: result 0 keeps the lower partner's value, result 1 the upper partner's).
+template <int O>
+__device__ __forceinline__ float pair_sum(const float x) {
+    const unsigned u = __float_as_uint(x);
+    if (O == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+}
 __device__ __forceinline__ float group_sum(float x, const int LPR) {
     if (LPR >= 2) x += dpp_lane<0xB1>(x);     // quad_perm [1,0,3,2]
     if (LPR >= 4) x += dpp_lane<0x4E>(x);     // quad_perm [2,3,0,1]
     if (LPR >= 8) x += dpp_lane<0x141>(x);    // row_half_mirror: lane i <- lane 7-i of its half row
     if (LPR >= 16) x += dpp_lane<0x140>(x);   // row_mirror: lane i <- lane 15-i of its row
-    if (LPR >= 32) x += __shfl_xor(x, 16, 64);
-    if (LPR >= 64) x += __shfl_xor(x, 32, 64);
+    if (LPR >= 32) x = pair_sum<16>(x);
+    if (LPR >= 64) x = pair_sum<32>(x);
     return x;
 }
 
