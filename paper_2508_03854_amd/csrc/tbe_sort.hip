@@ -157,7 +157,7 @@ hipError_t launch_linearize(const tbe_handle* h, const void* indices_p, const vo
 // =================================================================================================
 constexpr int kRsThreads = 256;
 constexpr int kRsWaves = kRsThreads / kWave;
-constexpr int kRsItems = kRadixTile / kRsThreads;  // 8
+constexpr int kRsItems = kRadixTile / kRsThreads;  // 16 keys per thread and tile
 constexpr int kRsBins = 256;
 
 struct SortPlan {
