@@ -152,3 +152,16 @@ def test_sequence_edge_cases(H):
     assert tbe.poll_index_error()
     assert torch.equal(flat, before) and float(state.abs().max()) == 0.0
     tbe.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_sequence_tables_of_every_width_class(H, dtype):
+    # rows of 8 to 1024 columns in one handle: both row-update kernels in the non-pooled layout, with rows that take
+    # hundreds of lookups in a narrow and in a wide table
+    v = 8 if dtype == "f16" else 4
+    cfg = W.Config("seqmix", [40, 300, 9, 1000, 6], [1024, 2 * v, 512 + v, 64, 256], dtype, 512, "sum",
+                   ("poisson1", 6.0), ("zipf", 1.1))
+    cfg.c = 2.0
+    reps = run_seq(H, cfg, "f32", torch.int64)
+    print("seqmix", dtype, reps, flush=True)
+    assert reps[0]["U"] > 300
