@@ -525,12 +525,18 @@ __global__ __launch_bounds__(kRleThreads) void rle_count_kernel(const uint32_t* 
                                                                 uint32_t* __restrict__ block_counts) {
     __shared__ uint32_t s_w[kRleThreads / kWave];
     const int64_t base = (int64_t)blockIdx.x * kRleTile;
-    uint32_t c = 0;
+    uint32_t c = 0;   // heads seen by this wavefront: one ballot and one population count per run of 64 keys
 #pragma unroll
-    for (int k = 0; k < kRleItems; ++k) c += is_head(keys, base + k * kRleThreads + threadIdx.x, N) ? 1u : 0u;
-    uint32_t tot;
-    (void)block_excl_scan<kRleThreads>(c, s_w, &tot);
-    if (threadIdx.x == 0) block_counts[blockIdx.x] = tot;
+    for (int k = 0; k < kRleItems; ++k)
+        c += (uint32_t)__popcll(__ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N)));
+    if (lane_id() == 0) s_w[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tot = 0;
+#pragma unroll
+        for (int w = 0; w < kRleThreads / kWave; ++w) tot += s_w[w];
+        block_counts[blockIdx.x] = tot;
+    }
 }
 
 // single block: exclusive scan of the per-tile head counts in place; writes num_unique, the closing
