@@ -22,6 +22,14 @@ constexpr int kFwdThreads = 256;
 #define TBE_FWD_WAVES 8
 #endif
 
+// Lane-group classes: a bag with more ids than this is walked by a whole wavefront instead of one lane group.  The
+// more bags share a wavefront, the more lanes one long bag keeps waiting, so the bound falls with the lanes per row
+// (measured at lognormal bag lengths, 8 bags per wavefront: 2.28 ms without, 2.07 / 2.01 / 1.94 / 1.86 ms at 96 / 64 /
+// 48 / 32; a bound below the typical length would send ordinary bags the slower way).
+__device__ __host__ __forceinline__ int long_bag_min(const int lanes_per_row) {
+    return lanes_per_row > 16 ? 64 : (lanes_per_row > 8 ? 48 : 32);
+}
+
 // NC = number of 64-lane column chunks a row needs (1 when D <= 64 * kVec); U = rows in flight per group.
 template <typename WT, int NC, int U, bool MEAN>
 __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const int D, const int64_t R,
@@ -161,7 +169,11 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
         start = start < 0 ? 0 : (start > nnz ? nnz : start);
         end = end < start ? start : (end > nnz ? nnz : end);
     }
-    const int len = (int)((end - start) < (int64_t)0x7FFFFFFF ? (end - start) : (int64_t)0x7FFFFFFF);
+    const int full_len = (int)((end - start) < (int64_t)0x7FFFFFFF ? (end - start) : (int64_t)0x7FFFFFFF);
+    // a bag far longer than its neighbours would keep the other groups of the wavefront waiting: such bags are left to
+    // forward_long_bags_kernel, where a whole wavefront walks one bag
+    const bool is_long = full_len > long_bag_min(LPR);
+    const int len = is_long ? 0 : full_len;
     const int maxlen = wave_max_i32(len);   // longest bag of the wavefront: the loop bounds below are wave-uniform
     float acc[V];
 #pragma unroll
@@ -190,12 +202,61 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
     }
     float scale = 1.f;
     if (MEAN) scale = len > 0 ? 1.f / (float)len : 0.f;
-    if (has_bag && col_on) {
+    if (has_bag && col_on && !is_long) {
         const int64_t out_elem = b * (int64_t)sumD + d0 + lc;
 #pragma unroll
         for (int v4 = 0; v4 < V; v4 += 4)
             store4_from_float(out, out_io, out_elem + v4, acc[v4] * scale, acc[v4 + 1] * scale, acc[v4 + 2] * scale,
                               acc[v4 + 3] * scale);
+    }
+}
+
+// The long bags of the lane-group classes.  A wavefront looks at kLongScan x 64 consecutive bags of one table, 64 at
+// a time with one bag per lane, and walks every bag with more than long_bag_min ids with all of its lanes
+// (forward_bag, as for wide rows).  A kernel of its own: inside the lane-group kernel the second phase pushed the
+// binary16 variant over its 64 registers (8.0 -> 9.3 ms at the largest workload).
+constexpr int kLongScan = 4;
+template <typename WT, bool MEAN>
+__global__ __launch_bounds__(kFwdThreads, 4) void forward_long_bags_kernel(
+    const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
+    const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
+    const int32_t* __restrict__ tables_of_class, const int32_t n_tables, const int32_t B, const int64_t nnz,
+    const int32_t sumD, void* __restrict__ out, const int out_io, int32_t* err) {
+    constexpr int V = RowIO<WT>::kVec;
+    const int lane = lane_id();
+    const int64_t per_table = ((int64_t)B + kLongScan * kWave - 1) / (kLongScan * kWave);   // wavefronts per table
+    const int64_t wid = (int64_t)blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t i = wid / per_table;
+    if (i >= n_tables) return;
+    const int32_t t = tables_of_class[i];
+    const int32_t d0 = D_off[t];
+    const int D = D_off[t + 1] - d0;
+    // the bound of the table's class: lanes per row as the host classifies them (power of two, at least 4)
+    const int nl = (D + V - 1) / V;
+    const int bound = long_bag_min(nl > 16 ? 32 : (nl > 8 ? 16 : (nl > 4 ? 8 : 4)));
+    for (int q = 0; q < kLongScan; ++q) {
+        const int64_t b0 = ((wid - i * per_table) * kLongScan + q) * kWave;   // first bag of this round (wave-uniform)
+        if (b0 >= B) break;
+        const int64_t b = b0 + lane;
+        int64_t start = 0, end = 0;
+        if (b < B) {   // clamped as in the lane-group kernel
+            const int64_t bag = (int64_t)t * B + b;
+            start = offsets[bag];
+            end = offsets[bag + 1];
+            start = start < 0 ? 0 : (start > nnz ? nnz : start);
+            end = end < start ? start : (end > nnz ? nnz : end);
+        }
+        uint64_t todo = __ballot(end - start > (int64_t)bound);
+        while (todo != 0ull) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1ull;
+            const int64_t s = (int64_t)(((uint64_t)bcast_lane((uint32_t)((uint64_t)start >> 32), src) << 32) |
+                                        (uint64_t)bcast_lane((uint32_t)((uint64_t)start & 0xFFFFFFFFull), src));
+            const int64_t e = (int64_t)(((uint64_t)bcast_lane((uint32_t)((uint64_t)end >> 32), src) << 32) |
+                                        (uint64_t)bcast_lane((uint32_t)((uint64_t)end & 0xFFFFFFFFull), src));
+            forward_bag<WT, 1, TBE_FWD_U, MEAN>(weights + w_off[t], D, row_base[t + 1] - row_base[t], indices, s, e, out,
+                                                out_io, (b0 + src) * (int64_t)sumD + d0, err);
+        }
     }
 }
 
@@ -238,6 +299,19 @@ static void launch_forward_groups(const tbe_handle* h, const void* tables, const
         else
             forward_groups_kernel<WT, TBE_FWD_GROUP_U, false><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
+    }
+    // the bags those launches left out (the four classes' tables follow one another in the list)
+    const int n_all = h->fwd_count[1] + h->fwd_count[2] + h->fwd_count[3] + h->fwd_count[4];
+    if (n_all > 0) {
+        const int64_t waves = (int64_t)n_all * (((int64_t)B + kLongScan * kWave - 1) / (kLongScan * kWave));
+        const dim3 grid((unsigned)((waves + wpb - 1) / wpb));
+        const int32_t* list = h->d_fwd_tables + h->fwd_first[1];
+        if (mean)
+            forward_long_bags_kernel<WT, true><<<grid, kFwdThreads, 0, s>>>(
+                w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n_all, B, nnz, h->sumD, out, out_io, h->d_err);
+        else
+            forward_long_bags_kernel<WT, false><<<grid, kFwdThreads, 0, s>>>(
+                w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n_all, B, nnz, h->sumD, out, out_io, h->d_err);
     }
 }
 

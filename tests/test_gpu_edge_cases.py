@@ -531,3 +531,23 @@ def test_prepare_then_apply_equals_the_one_call_backward(name, kw, idt):
     with pytest.raises(TbeError):
         tbe.backward_apply_rowwise_adagrad(gout, off, cfg.B, idx.numel(), f2, s2, ws[:1024], **kwargs)
     tbe.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_bag_lengths_around_the_long_bag_bounds(H, dtype):
+    # narrow rows take one bag per lane group unless the bag is long (more than 32 / 48 / 64 ids by lanes per row), in
+    # which case a whole wavefront walks it: lengths on both sides of every bound, in every narrow-row class,
+    # next to empty and short bags in the same wavefront
+    rng = np.random.default_rng(41)
+    v = 8 if dtype == "f16" else 4
+    D = [v, 2 * v, 4 * v, 8 * v, 16 * v, 32 * v]          # 1 .. 32 lanes per row
+    rows = [11, 60, 500, 37, 900, 64]
+    B = 150
+    cfg = make_cfg(rows, D, dtype=dtype, B=B, pooling="mean", c=2.0)
+    special = [0, 1, 31, 32, 33, 47, 48, 49, 63, 64, 65, 66, 130, 500]
+    lens = rng.integers(0, 9, size=len(D) * B)
+    for t in range(len(D)):
+        where = rng.choice(B, size=len(special), replace=False)
+        lens[t * B + where] = special
+    ids = np.concatenate([rng.integers(0, rows[t], size=int(lens[t * B:(t + 1) * B].sum())) for t in range(len(D))])
+    run_custom(H, cfg, lens, ids)
