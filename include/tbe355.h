@@ -183,7 +183,10 @@ tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, siz
  *                     bag-major and the sort is stable); after a non-pooled call the original position p
  *                     (ascending inside a run of equal keys)
  *   unique_rows[*num_unique] ascending, seg_start[*num_unique + 1] (seg_start[U] = nnz), num_unique[1].
- * Invalid ids, if any, appear as one trailing pseudo-row with key sum(rows).  Non-pooled calls: pass B = 1. */
+ * Invalid ids, if any, carry the key sum(rows) and form pseudo-rows that no kernel updates: one trailing pseudo-row,
+ * or - when the handle sorts table by table, which tbe_create decides from the table sizes - one at the end of
+ * every table's run that has invalid ids (keys_sorted is then ascending among the valid ids only).
+ * Non-pooled calls: pass B = 1. */
 tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int64_t nnz,
                             const uint32_t** keys_sorted, const uint32_t** vals_sorted, const uint32_t** unique_rows,
                             const uint32_t** seg_start, const uint32_t** num_unique);
