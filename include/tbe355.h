@@ -57,7 +57,9 @@ typedef enum { TBE_I64 = 0, TBE_I32 = 1 } tbe_index_dtype;                   /* 
 typedef enum { TBE_IO_F32 = 0, TBE_IO_F16 = 1, TBE_IO_BF16 = 2 } tbe_io_dtype; /* pooled output / upstream gradient */
 
 /* Describe the table set.  rows, D: HOST arrays of T entries.  Builds D_offsets / row_base / table
- * offsets on the current device.  The handle can be used by one stream at a time. */
+ * offsets on the current device.  One host thread at a time may make calls on a handle; calls on different
+ * streams may overlap on the device as long as they do not share a workspace or write the same tables (all they
+ * share in the handle is read-only metadata and the sticky invalid-id flag). */
 tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtype weight_dtype, tbe_handle** out);
 tbe_status tbe_destroy(tbe_handle* h);
 
