@@ -599,7 +599,10 @@ __global__ __launch_bounds__(kSegThreads) void seg_dense_bounds_kernel(const Seg
     }
 }
 
-constexpr int kDenseU = 2;   // gradient rows in flight per lane group
+#ifndef TBE_DENSE_U
+#define TBE_DENSE_U 3
+#endif
+constexpr int kDenseU = TBE_DENSE_U;   // gradient rows in flight per lane group
 template <bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_dense_partial_kernel(const SegArgs a) {
     __shared__ uint32_t s_cnt[kSegThreads / kWave][kWave][kDenseRows];   // per wavefront: counts of a block of 64 bags
