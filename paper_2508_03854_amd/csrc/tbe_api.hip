@@ -159,6 +159,15 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
         h->sort_bits = h->segmented ? local_bits : h->key_bits;
         h->sort_passes = (h->sort_bits + 7) / 8;
     }
+    {   // row-weighted share of the rows as wide as a wavefront (129..256 columns) among the tables up to 256 columns
+        double wide = 0.0, all = 0.0;
+        for (int t = 0; t < T; ++t) {
+            if (D[t] > 256) continue;
+            all += (double)rows[t];
+            if (D[t] > 128) wide += (double)rows[t];
+        }
+        h->seg_mostly_wavefront_rows = all > 0.0 && wide >= 0.5 * all;
+    }
     if (hipGetDevice(&h->device) != hipSuccess) {
         delete h;
         return TBE_EHIP;

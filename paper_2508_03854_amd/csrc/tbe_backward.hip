@@ -17,11 +17,17 @@
 namespace tbe {
 
 constexpr int kSegThreads = 256;
-constexpr int kSegBlocks = 2048;  // persistent grid: waves stride over blocks of 64 unique rows
-#ifndef TBE_SEG_U
-#define TBE_SEG_U 4
-#endif
-constexpr int kSegUnroll = TBE_SEG_U;
+constexpr int kSegBlocks = 2048;  // persistent grids: waves stride over blocks of 64 unique rows, or over rows
+// Gradient fragments in flight per lane while a row is reduced: as many as the registers of the variant allow
+// without spilling at the WAVES wavefronts per SIMD its kernel is compiled for.  Measured at the largest workload with
+// 32-bit gradients: 2 / 4 / 6 / 8 in flight give 21.6 / 20.4 / 20.2 / 19.8 ms for the row updates; 8 needs more than
+// the 64 registers of 8 wavefronts per SIMD, which is why seg_update runs 7 (6: 20.7 ms); 16-bit fragments are half
+// the size.
+template <int NC, bool MEAN, typename GT, int WAVES>
+__device__ __host__ constexpr int seg_unroll() {
+    return NC > 1 ? 4 : (sizeof(GT) == 4 ? (WAVES < 8 ? (MEAN ? 6 : 8) : (MEAN ? 4 : 6)) : 8);
+}
+
 #ifndef TBE_LONG_BLOCKS
 #define TBE_LONG_BLOCKS 2048
 #endif
@@ -115,11 +121,12 @@ __device__ __forceinline__ GradAddr grad_addr(const SegArgs& a, const int t, con
 // Whole-wavefront reduction of sorted positions [s, e) of ONE row:
 // acc += sum of scale(bag) * grad_out[b, d0 + col .. col+3]; the groups take interleaved positions and
 // fold_groups() completes the sum.  NC = 256-column chunks per row.
-template <int NC, bool MEAN, typename GT>
+template <int NC, bool MEAN, typename GT, int WAVES = 8>
 __device__ __forceinline__ void segment_reduce(float (&acc)[NC][4], const RowGeom& g, const GT* __restrict__ gcol,
                                                const int64_t sumD, const int64_t bag0,
                                                const uint32_t* __restrict__ bag_sorted, const IdxView offsets,
                                                const uint32_t s, const uint32_t e) {
+    constexpr int kSegUnroll = seg_unroll<NC, MEAN, GT, WAVES>();
     const int lane = lane_id();
     for (uint32_t base = s; base < e; base += kWave) {
         const int n = (int)((e - base) < (uint32_t)kWave ? (e - base) : (uint32_t)kWave);
@@ -708,8 +715,11 @@ __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_den
 }
 
 // ---- 3a. rows with at most kSegChunk lookups, all tables at most 256 columns wide ------------------
-template <typename WT, bool MEAN, typename GT>
-__global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+// kSegWaves = wavefronts per SIMD the kernel is compiled and launched for: 8, or 7 with more fragments in flight; the
+// host picks (see the launch).
+template <typename WT, bool MEAN, typename GT, int kSegWaves>
+__global__ __launch_bounds__(kSegThreads, kSegWaves) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+    constexpr int kSegUnroll = seg_unroll<1, MEAN, GT, kSegWaves>();
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
@@ -759,7 +769,7 @@ __global__ __launch_bounds__(kSegThreads, 8) void seg_update_kernel(const SegArg
                 const float v_r = bcast_lane(v, r);
                 float acc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
                 const GradAddr ga = grad_addr(a, t_r, g.D);
-                segment_reduce<1, MEAN, GT>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0,
+                segment_reduce<1, MEAN, GT, kSegWaves>(acc, g, static_cast<const GT*>(a.grad_out) + ga.base, ga.pitch, ga.row0,
                                             a.bag_sorted, a.offsets, s_r, s_r + len_r);
                 fold_groups<1>(acc, g);
                 WT* wrow = tables + a.w_off[t_r] + ((int64_t)key_r - a.row_base[t_r]) * g.D;
@@ -986,12 +996,22 @@ static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* 
                                bool wide, hipStream_t s) {
     const bool f32 = h->dtype == TBE_F32;
     if (narrow) {
-        if (f32) {
-            if (mean) seg_update_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            else seg_update_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+        // every CU filled once; 7 wavefronts per SIMD for 32-bit gradients on binary16 tables when most of their rows
+        // are as wide as the wavefront (measured: 20.2 -> 19.8 ms there, but 2.43 -> 2.55 ms on fp32 tables of the
+        // same widths, which therefore keep 8)
+        if (sizeof(GT) == 4 && !f32 && h->seg_mostly_wavefront_rows) {
+            const unsigned grid = 256u * 7u;
+            if (mean) seg_update_kernel<__half, true, GT, 7><<<grid, kSegThreads, 0, s>>>(a, counters);
+            else seg_update_kernel<__half, false, GT, 7><<<grid, kSegThreads, 0, s>>>(a, counters);
         } else {
-            if (mean) seg_update_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            else seg_update_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            const unsigned grid = 256u * 8u;
+            if (f32) {
+                if (mean) seg_update_kernel<float, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_kernel<float, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+            } else {
+                if (mean) seg_update_kernel<__half, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+                else seg_update_kernel<__half, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+            }
         }
     }
     if (wide) {

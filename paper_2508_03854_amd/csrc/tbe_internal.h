@@ -60,6 +60,7 @@ struct tbe_handle {
     int32_t sumD = 0;
     int32_t maxD = 0;
     int32_t minD = 0;
+    bool seg_mostly_wavefront_rows = false;  // most rows of the tables up to 256 columns need all 64 lanes (D > 128)
     int key_bits = 1;  // bits needed to hold the value total_rows (the key given to invalid ids)
     // Sort plan.  Positions arrive grouped by table, so sorting every table's run of positions on its table-local id
     // alone gives the same order as sorting all of them on the linearised key, with fewer key bits whenever
