@@ -29,7 +29,7 @@ MEASURED_TRAFFIC_BYTES = {
     # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per step under one timing record
     # (a record with several launches per step carries their sum).  The counters sit behind the L2: they count what the
     # L2 asked of the fabric, whether the Infinity Cache or HBM served it.
-    ("C4", "seg_update"): 131.70e9,
+    ("C4", "seg_update"): 131.09e9,
     ("C4", "forward_pool"): 41.52e9,          # the forward launches (32- and 16-lane rows, long-bag scan)
     ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep)
     ("C4", "seg_dense_partial"): 8.52e9,
