@@ -212,6 +212,23 @@ tbe_status tbe_timing_read(tbe_handle* h, int32_t i, const char** name, float* m
  * streaming bandwidth next to the published peak.  Recorded by the timing facility as "calibration_copy". */
 tbe_status tbe_calibration_copy(tbe_handle* h, void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* Measurement aid, not a step of the method: `gathers` slices of `slice_bytes` bytes each (a power of two, 16 ..
+ * 1024) are read from pseudo-random, slice-aligned places of a window of `window_bytes` bytes (a power of two) of
+ * `buf`; with write_back != 0 every slice is written back changed (a read-modify-write, as the row update does).
+ * This is the access pattern of the embedding kernels - one table row or one gradient slice per lookup - with the
+ * traffic known by construction: gathers * slice_bytes read (and as much written).  The compute die is made of 8
+ * partitions with a level-2 cache each, and workgroup i runs on partition i mod 8: with per_xcd != 0 partition x
+ * draws its eighth of the slices from a window of its own, buf + x * window_bytes, so that `window_bytes` is the
+ * working set of one level-2 cache; with per_xcd == 0 all draw from the one window at buf.  Places are a bijection
+ * of the slice number, so up to window_bytes / slice_bytes slices per window are distinct; reads may exceed that
+ * (they then repeat, which is what a window smaller than a cache is for), written-back slices may not (TBE_ESHAPE).
+ *   buf   DEVICE, 16-byte aligned, buf_bytes >= window_bytes * (per_xcd ? 8 : 1); contents are scratch
+ *   sink  DEVICE, 16-byte aligned, sink_bytes >= 2 MiB; receives one checksum word per lane
+ * Recorded by the timing facility as "calibration_gather". */
+tbe_status tbe_calibration_gather(tbe_handle* h, void* buf, size_t buf_bytes, size_t window_bytes, int32_t per_xcd,
+                                  int32_t slice_bytes, int64_t gathers, int32_t write_back, void* sink,
+                                  size_t sink_bytes, void* hip_stream);
+
 const char* tbe_status_string(tbe_status s);
 
 #ifdef __cplusplus

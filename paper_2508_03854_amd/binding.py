@@ -26,7 +26,7 @@ EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "t
            "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_prepare",
            "tbe_backward_apply_rowwise_adagrad", "tbe_backward_apply_sgd", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
            "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable",
-           "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_status_string"]
+           "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_calibration_gather", "tbe_status_string"]
 
 
 class TbeError(RuntimeError):
@@ -97,6 +97,9 @@ def load_library():
     L.tbe_timing_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(f32)]
     L.tbe_calibration_copy.restype = ctypes.c_int
     L.tbe_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
+    L.tbe_calibration_gather.restype = ctypes.c_int
+    L.tbe_calibration_gather.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_size_t, i32, i32, i64, i32, vp,
+                                         ctypes.c_size_t, vp]
     L.tbe_status_string.restype = ctypes.c_char_p
     L.tbe_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -428,6 +431,18 @@ class TBE:
             raise ValueError("dst and src must be device tensors of the same byte size")
         _check(self._lib.tbe_calibration_copy(self._h, dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)),
                "tbe_calibration_copy")
+
+    # ---- tbe_calibration_gather
+    def calibration_gather(self, buf: torch.Tensor, window_bytes: int, slice_bytes: int, gathers: int, *,
+                           per_xcd: bool = True, write_back: bool = False, sink: torch.Tensor,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+        if not (buf.is_cuda and sink.is_cuda):
+            raise ValueError("buf and sink must be device tensors")
+        _check(self._lib.tbe_calibration_gather(self._h, buf.data_ptr(), buf.numel() * buf.element_size(),
+                                                int(window_bytes), 1 if per_xcd else 0, int(slice_bytes), int(gathers),
+                                                1 if write_back else 0, sink.data_ptr(),
+                                                sink.numel() * sink.element_size(), _stream_ptr(stream)),
+               "tbe_calibration_gather")
 
     # ---- tbe_timing_*
     def timing_enable(self, on: bool = True) -> None:

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtbe355.so")
-SOURCES = ["tbe_api.hip", "tbe_forward.hip", "tbe_sort.hip", "tbe_backward.hip", "tbe_sync.hip"]
+SOURCES = ["tbe_api.hip", "tbe_forward.hip", "tbe_sort.hip", "tbe_backward.hip", "tbe_sync.hip", "tbe_calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,7 +30,7 @@ def build(force: bool = True, verbose: bool = False, defines=(), lib: str = LIB,
     """defines / lib / obj_dir let an experiment build a variant (-DNAME=VALUE) into another file."""
     OBJ, LIB = obj_dir, lib  # noqa: N806 - shadow the defaults
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".cuh"))]
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(ROOT, "include", "tbe355.h"))
 
     def compile_one(src: str) -> str:

@@ -83,12 +83,6 @@ void LaunchTimer::done() {
     if (slot >= 0) (void)hipEventRecord(h->slots[slot].end, s);
 }
 
-__global__ __launch_bounds__(256) void calibration_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
-                                                               const size_t n) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
-}
-
 static int bits_for(uint64_t v) {  // number of bits needed to represent v (>= 1)
     int b = 1;
     while ((v >> b) != 0) ++b;
@@ -199,6 +193,7 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     h->d_row_base = reinterpret_cast<int64_t*>(base + b_doff);
     h->d_w_off = reinterpret_cast<int64_t*>(base + b_doff + b_rb);
     h->d_err = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo);
+    h->d_zero = base + b_doff + b_rb + b_wo + 128;
     h->d_fwd_tables = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo + 256);
     bool ok = hipMemset(h->d_meta, 0, total) == hipSuccess;
     ok = ok && hipMemcpy(h->d_fwd_tables, cls_tables.data(), 4 * (size_t)T, hipMemcpyHostToDevice) == hipSuccess;
@@ -417,16 +412,6 @@ tbe_status tbe_poll_index_error(tbe_handle* h) {
         return TBE_EINDEX;
     }
     return TBE_OK;
-}
-
-tbe_status tbe_calibration_copy(tbe_handle* h, void* dst, const void* src, size_t bytes, void* hip_stream) {
-    if (!h || !dst || !src || (bytes & 15) != 0 || !aligned(dst, 16) || !aligned(src, 16)) return TBE_EINVAL;
-    if (bytes == 0) return TBE_OK;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LaunchTimer tm(h, s, "calibration_copy");
-    calibration_copy_kernel<<<256 * 16, 256, 0, s>>>(static_cast<float4*>(dst), static_cast<const float4*>(src), bytes / 16);
-    tm.done();
-    return hipGetLastError() == hipSuccess ? TBE_OK : TBE_EHIP;
 }
 
 tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, size_t count, tbe_dtype dtype,

@@ -11,7 +11,7 @@
 //   - long   (> kSegChunk lookups, the head of the Zipf distribution): cut into chunks that separate
 //     wavefronts reduce into a partial buffer, combined in chunk order by the row's owner.
 // Row metadata (segment bounds, key, table, moment) is fetched for 64 rows at a time, one row per lane.
-#include "tbe_device.cuh"
+#include "tbe_device.h"
 #include "tbe_internal.h"
 
 namespace tbe {
@@ -70,6 +70,7 @@ struct SegArgs {
     uint32_t* counters_rw;        // the same words, for the kernels that bump them
     const uint32_t* bag_sorted;   // the sorted payload: linear bag id of every sorted lookup
     IdxView offsets;
+    const void* zeros;            // 128 bytes of zeros, never written
     const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT (or the sequence layout)
     const int64_t* seq_gbase;     // non-pooled mode only: element offset of table t's gradient block minus start_t * D_t
     int seq;                      // 1: non-pooled; bag_sorted then holds the original positions
@@ -187,6 +188,13 @@ __device__ __forceinline__ void fold_groups(float (&acc)[NC][4], const RowGeom& 
     }
 }
 
+// the step size of Algorithm 1, step 6: lr / (sqrt(v / c) + eps), from the hardware square root and reciprocal (one
+// unit in the last place each); v == 0 means the row's gradient is zero and nothing is applied
+__device__ __forceinline__ float adagrad_step(const float v_new, const float lr, const float eps, const float inv_c) {
+    const float denom = __builtin_amdgcn_sqrtf(v_new * inv_c) + eps;
+    return v_new > 0.f ? lr * __builtin_amdgcn_rcpf(denom) : 0.f;
+}
+
 // The optimizer step for one row.  acc holds the complete row gradient in the LPR lanes that `on`
 // marks (all groups after fold_groups, or each group its own row).  v_old is the row's moment.
 //   v <- v + ||g||^2 ;  w <- w - lr / (sqrt(v / c) + eps) * g      (updated v; v stored unscaled)
@@ -207,8 +215,7 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
     }
     sq = group_sum(sq, g.LPR);  // within the LPR lanes that cover the row
     const float v_new = v_old + sq;
-    const float denom = sqrtf(v_new * inv_c) + eps;
-    const float step = sgd ? lr : (v_new > 0.f ? lr / denom : 0.f);  // v_new == 0 means g == 0: nothing to apply
+    const float step = sgd ? lr : adagrad_step(v_new, lr, eps, inv_c);
     if (write) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -1084,6 +1091,7 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[spare ^ 1]);   // the sorted payload stream
     a.offsets = IdxView{offsets, idx32};
     a.grad_out = grad_out;
+    a.zeros = h->d_zero;
     a.D_off = h->d_D_off;
     a.row_base = h->d_row_base;
     a.w_off = h->d_w_off;

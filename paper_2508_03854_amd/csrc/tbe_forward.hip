@@ -6,7 +6,7 @@
 // lane; the groups walk the bag in an interleaved fashion, four rows per group in flight, and a
 // butterfly over the groups folds the partial sums at the end.  The bag's ids are read with one
 // coalesced 64-wide load and handed to the groups with cross-lane reads.
-#include "tbe_device.cuh"
+#include "tbe_device.h"
 #include "tbe_internal.h"
 
 namespace tbe {

@@ -1,6 +1,6 @@
 // Integer half of the backward pass: linearise ids into row keys, stable LSD radix sort of (key, payload) with the
 // lookup's bag id (pooled calls) or position (non-pooled calls) as payload, run-length segmentation into unique rows.  Everything here is exact integer work.
-#include "tbe_device.cuh"
+#include "tbe_device.h"
 #include "tbe_internal.h"
 
 namespace tbe {

@@ -4,7 +4,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
-#include "tbe_device.cuh"
+#include "tbe_device.h"
 #include "tbe_internal.h"
 
 namespace tbe {
