@@ -115,6 +115,8 @@ def main():
                     help="replay one captured HIP graph per pooled batch instead of launching every kernel (small, "
                          "launch-bound workloads)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
+    ap.add_argument("--hot-rows-min-workgroups", type=int, default=None,
+                    help="tunable of the forward's on-chip hot-row path (negative: off; default: the library's)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures ONE GPU: this path has no collectives (the cross-replica weight/moment averaging and "
@@ -153,6 +155,8 @@ def main():
     out = torch.empty(cfg.B, cfg.sum_D, dtype=io_t, device=dev)
     max_nnz = max(int(i.numel()) for i, _ in batches)
     tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    if args.hot_rows_min_workgroups is not None:
+        tbe.set_tunable("hot_rows_min_workgroups", args.hot_rows_min_workgroups)
     ws = tbe.alloc_workspace(cfg.B, max_nnz)
     torch.cuda.synchronize()
     log(f"inputs ready in {time.time() - t0:.1f}s; nnz/batch ~ {max_nnz}; workspace {ws.numel() / 1e6:.1f} MB")

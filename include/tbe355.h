@@ -74,7 +74,9 @@ tbe_status tbe_workspace_bytes(const tbe_handle* h, int32_t B, int64_t max_nnz, 
  *   tables    DEVICE  flat weights (float or IEEE binary16 per the handle's dtype), 16-byte aligned
  *   D_offsets DEVICE  int32 [T+1], or NULL to use the handle's own copy
  *   indices   DEVICE  int64 [nnz];  offsets DEVICE int64 [T*B+1]
- *   out       DEVICE  float [B, sum(D)], 16-byte aligned, fully overwritten */
+ *   out       DEVICE  float [B, sum(D)], 16-byte aligned, fully overwritten
+ * Order of the additions inside a bag: fixed for given inputs and a given hot-row hint in the handle (see
+ * tbe_set_tunable); the hint is rewritten by every backward call on the handle. */
 tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D_offsets, const int64_t* indices,
                        const int64_t* offsets, int32_t B, int64_t nnz, tbe_pooling pooling, float* out,
                        void* hip_stream);
@@ -195,6 +197,16 @@ tbe_status tbe_debug_sorted(const tbe_handle* h, void* workspace, int32_t B, int
 
 /* Synchronises the device, reads and clears the sticky invalid-id flag.  Returns TBE_EINDEX if it was set. */
 tbe_status tbe_poll_index_error(tbe_handle* h);
+
+/* Tunables of a handle (host-side settings read by later calls; none changes any result beyond the order of
+ * floating-point additions).
+ *   TBE_TUNE_HOT_ROWS_MIN_WORKGROUPS  The forward keeps, for every table, a copy of the rows that had the most lookups
+ *       in the LAST backward call on this handle in on-chip memory (the handle remembers their ids: a hint, the
+ *       pooled sums are the same whatever it holds) and serves their lookups from there.  That path runs for a group
+ *       of tables of one width when it fills at least `value` workgroups (default 256, one per compute unit; 0:
+ *       whenever the width allows it; negative: never). */
+typedef enum { TBE_TUNE_HOT_ROWS_MIN_WORKGROUPS = 0 } tbe_tunable;
+tbe_status tbe_set_tunable(tbe_handle* h, tbe_tunable which, int64_t value);
 
 /* Per-kernel timing with HIP events on the stream the kernels run on.  tbe_timing_enable(h, 1) clears
  * the record and turns timing on: from then on every kernel that a forward/backward call launches is

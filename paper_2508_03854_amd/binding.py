@@ -18,6 +18,7 @@ F32, F16 = 0, 1
 SUM, MEAN = 0, 1
 I64, I32 = 0, 1                       # tbe_index_dtype
 IO_F32, IO_F16, IO_BF16 = 0, 1, 2     # tbe_io_dtype
+TUNABLES = {"hot_rows_min_workgroups": 0}   # tbe_tunable
 _IDX = {torch.int64: I64, torch.int32: I32}
 _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 
@@ -25,7 +26,7 @@ _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
            "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_prepare",
            "tbe_backward_apply_rowwise_adagrad", "tbe_backward_apply_sgd", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
-           "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_timing_enable",
+           "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_set_tunable", "tbe_timing_enable",
            "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_calibration_gather", "tbe_status_string"]
 
 
@@ -89,6 +90,8 @@ def load_library():
     L.tbe_debug_sorted.argtypes = [vp, vp, i32, i64] + [ctypes.POINTER(vp)] * 5
     L.tbe_poll_index_error.restype = ctypes.c_int
     L.tbe_poll_index_error.argtypes = [vp]
+    L.tbe_set_tunable.restype = ctypes.c_int
+    L.tbe_set_tunable.argtypes = [vp, ctypes.c_int, i64]
     L.tbe_timing_enable.restype = ctypes.c_int
     L.tbe_timing_enable.argtypes = [vp, ctypes.c_int]
     L.tbe_timing_count.restype = ctypes.c_int
@@ -443,6 +446,10 @@ class TBE:
                                                 1 if write_back else 0, sink.data_ptr(),
                                                 sink.numel() * sink.element_size(), _stream_ptr(stream)),
                "tbe_calibration_gather")
+
+    # ---- tbe_set_tunable
+    def set_tunable(self, which: str, value: int) -> None:
+        _check(self._lib.tbe_set_tunable(self._h, TUNABLES[which], int(value)), "tbe_set_tunable")
 
     # ---- tbe_timing_*
     def timing_enable(self, on: bool = True) -> None:

@@ -168,7 +168,9 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     }
     const size_t b_doff = align256(4 * (size_t)(T + 1)), b_rb = align256(8 * (size_t)(T + 1)), b_wo = b_rb;
     const size_t b_cls = align256(4 * (size_t)T);
-    const size_t total = b_doff + b_rb + b_wo + 256 + b_cls;
+    const bool keep_hot = T <= kMaxSortSegments;
+    const size_t b_hot = keep_hot ? align256(4 * (size_t)T * kHotRows) + align256(4 * (size_t)T) : 0;
+    const size_t total = b_doff + b_rb + b_wo + 256 + b_cls + b_hot;
     std::vector<int32_t> cls_tables;
     {   // forward classes by lanes per row (D / elements per 16-byte fragment, rounded up to a power of two)
         const int vec = weight_dtype == TBE_F16 ? 8 : 4;
@@ -195,6 +197,10 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     h->d_err = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo);
     h->d_zero = base + b_doff + b_rb + b_wo + 128;
     h->d_fwd_tables = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo + 256);
+    if (keep_hot) {   // (zeroed below: no hot rows until a backward call has listed some)
+        h->d_hot_ids = reinterpret_cast<uint32_t*>(base + b_doff + b_rb + b_wo + 256 + b_cls);
+        h->d_hot_n = h->d_hot_ids + align256(4 * (size_t)T * kHotRows) / 4;
+    }
     bool ok = hipMemset(h->d_meta, 0, total) == hipSuccess;
     ok = ok && hipMemcpy(h->d_fwd_tables, cls_tables.data(), 4 * (size_t)T, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_D_off, h->D_off.data(), 4 * (size_t)(T + 1), hipMemcpyHostToDevice) == hipSuccess;
@@ -426,6 +432,14 @@ tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, siz
     if (count == 0 || M == 1) return TBE_OK;   // the mean over one replica is that replica
     const hipError_t e = launch_replica_mean(h, replicas, M, count, dtype == TBE_F32, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? TBE_OK : TBE_EHIP;
+}
+
+tbe_status tbe_set_tunable(tbe_handle* h, tbe_tunable which, int64_t value) {
+    if (!h) return TBE_EINVAL;
+    switch (which) {
+        case TBE_TUNE_HOT_ROWS_MIN_WORKGROUPS: h->hot_min_workgroups = value; return TBE_OK;
+    }
+    return TBE_EINVAL;
 }
 
 tbe_status tbe_timing_enable(tbe_handle* h, int enable) {

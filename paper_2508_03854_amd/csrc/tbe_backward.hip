@@ -367,6 +367,40 @@ __global__ __launch_bounds__(256) void seg_long_scan_kernel(const uint32_t* __re
     }
 }
 
+// ---- 1c. the hot-row hint for the next forward: per table the kHotRows rows with the most lookups ------------------
+// One workgroup per table ranks the table's long rows by their number of lookups (ties: smaller key first) and
+// leaves the table-local ids of the first kHotRows in the handle.  With more long rows than can be ranked the first
+// kHotRows of the list serve: the list is a hint, the forward gives the same result whatever it holds.
+constexpr int kHotMaxCand = 1024;
+__global__ __launch_bounds__(256) void hot_select_kernel(const SegArgs a, const uint32_t* __restrict__ tbase,
+                                                         uint32_t* __restrict__ hot_ids, uint32_t* __restrict__ hot_n) {
+    __shared__ uint32_t c_len[kHotMaxCand], c_key[kHotMaxCand];
+    const int t = blockIdx.x;
+    const uint4* list = reinterpret_cast<const uint4*>(a.long_list);
+    const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
+    const uint32_t i0 = tbase[t] < nlong ? tbase[t] : nlong, i1 = tbase[t + 1] < nlong ? tbase[t + 1] : nlong;
+    const uint32_t n = i1 - i0;
+    const uint32_t rb = (uint32_t)a.row_base[t];
+    uint32_t* ids = hot_ids + (size_t)t * kHotRows;
+    if (threadIdx.x == 0) hot_n[t] = n < (uint32_t)kHotRows ? n : (uint32_t)kHotRows;
+    if (n > (uint32_t)kHotMaxCand) {
+        for (uint32_t k = threadIdx.x; k < (uint32_t)kHotRows; k += blockDim.x) ids[k] = a.keys_unique[list[i0 + k].x] - rb;
+        return;
+    }
+    for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) {
+        const uint32_t u = list[i0 + k].x;
+        c_len[k] = a.seg_start[u + 1] - a.seg_start[u];
+        c_key[k] = a.keys_unique[u];
+    }
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) {
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < n; ++j)
+            rank += (c_len[j] > c_len[k] || (c_len[j] == c_len[k] && c_key[j] < c_key[k])) ? 1u : 0u;
+        if (rank < (uint32_t)kHotRows) ids[rank] = c_key[k] - rb;
+    }
+}
+
 // ---- 1d. work units in list (= table) order: unit (pos, c) for c < C(pos); one workgroup -------------
 __global__ __launch_bounds__(1024) void seg_long_units_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
     __shared__ uint32_t smem[1024 / kWave];
@@ -1141,6 +1175,7 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         LaunchTimer tm(h, s, "seg_long_list");
         seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
         seg_long_fill_kernel<<<512, 256, 0, s>>>(a, counters, tbase, tfill);
+        if (h->d_hot_ids && !seq) hot_select_kernel<<<h->T, 256, 0, s>>>(a, tbase, h->d_hot_ids, h->d_hot_n);
         if (dense) seg_dense_select_kernel<<<h->T, 256, 0, s>>>(a, tbase);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
         if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<2048, kSegThreads, 0, s>>>(a);   // (a chain of ~17 dependent loads per row: many waves)

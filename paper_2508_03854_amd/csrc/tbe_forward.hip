@@ -211,6 +211,172 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
     }
 }
 
+// ---- the lane-group classes with the tables' hottest rows held in LDS --------------------------------------------
+// In a skewed batch a hundred rows of a table take half of its lookups.  Their rows come from the L2, but every read
+// that leaves a compute unit's vector L1 occupies one of its few dozen miss slots for the length of the trip, and it
+// is those slots times the trip time that bound this kernel.  A workgroup of 16 wavefronts therefore takes a long run of
+// consecutive bags of ONE table, copies the rows that the handle lists as the table's hottest (the rows that had the
+// most lookups in the last backward call - a hint: any list of valid ids gives the same result) into LDS once, and
+// serves every lookup of one of those rows from there.  A lookup finds out through a small open-addressing table of
+// ids in LDS.  Per round of LPR ids a lane group first walks its cold ids (global loads, U rows in flight), then its
+// hot ones (LDS reads); the two lists are compacted through an LDS stage, so that no lane issues a load it does not
+// need.  The sum is taken in that order, which is fixed, so results do not depend on timing.
+constexpr int kHotThreads = 1024;
+constexpr int kHotWaves = kHotThreads / kWave;
+constexpr int kHotTab = 1024;                // slots of the id table (at most kHotRows ids: a quarter full)
+constexpr int kHotRowBytes = 64 << 10;       // LDS bytes for rows
+constexpr int kHotPasses = 16;               // rounds of kHotWaves * G bags per workgroup
+constexpr uint32_t kHotEmpty = 0xFFFFFFFFu;
+
+__device__ __forceinline__ uint32_t hot_hash(const uint32_t id) { return (id * 0x9E3779B1u) >> 22; }   // 10 bits
+
+template <typename WT, int U, bool MEAN>
+__global__ __launch_bounds__(kHotThreads, 8) void forward_hot_kernel(
+    const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
+    const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
+    const int32_t* __restrict__ tables_of_class, const int32_t n_tables, const int lpr_log2, const int32_t B,
+    const int64_t nnz, const int32_t sumD, void* __restrict__ out, const int out_io, int32_t* err,
+    const uint32_t* __restrict__ hot_ids, const uint32_t* __restrict__ hot_n, const int32_t chunks_per_table) {
+    constexpr int V = RowIO<WT>::kVec;
+    using raw_t = typename RowIO<WT>::raw_t;
+    __shared__ raw_t s_rows[kHotRowBytes / 16];
+    __shared__ uint32_t s_tab_id[kHotTab];
+    __shared__ uint16_t s_tab_slot[kHotTab];
+    __shared__ uint32_t s_cold[kHotWaves][kWave];
+    __shared__ uint16_t s_hot[kHotWaves][kWave];
+    const int lane = lane_id();
+    const int wv = threadIdx.x >> 6;
+    const int LPR = 1 << lpr_log2;
+    const int G = kWave >> lpr_log2;
+    const int32_t i = (int32_t)(blockIdx.x / (uint32_t)chunks_per_table);
+    const int32_t chunk = (int32_t)(blockIdx.x - (uint32_t)i * (uint32_t)chunks_per_table);
+    if (i >= n_tables) return;
+    const int32_t t = tables_of_class[i];
+    const int sub = lane >> lpr_log2;
+    const int li = lane & (LPR - 1);        // lane inside its group
+    const int lc = li * V;
+    const int32_t d0 = D_off[t];
+    const int D = D_off[t + 1] - d0;
+    const int64_t R = row_base[t + 1] - row_base[t];
+    const WT* table = weights + w_off[t];
+    const bool col_on = lc < D;
+    // ---- the table's hot rows: id table, then the rows themselves (one lane group per row)
+    int nh = (int)hot_n[t];
+    const int cap = (kHotRowBytes / 16) >> lpr_log2;
+    nh = nh > kHotRows ? kHotRows : nh;
+    nh = nh > cap ? cap : nh;
+    for (int k = threadIdx.x; k < kHotTab; k += kHotThreads) s_tab_id[k] = kHotEmpty;
+    __syncthreads();
+    if ((int)threadIdx.x < nh) {
+        const uint32_t id = hot_ids[(size_t)t * kHotRows + threadIdx.x];
+        if ((int64_t)id < R) {
+            uint32_t hsh = hot_hash(id);
+            for (;;) {   // ends: the table is at most a quarter full
+                const uint32_t old = atomicCAS(&s_tab_id[hsh], kHotEmpty, id);
+                if (old == kHotEmpty) {
+                    s_tab_slot[hsh] = (uint16_t)threadIdx.x;
+                    break;
+                }
+                if (old == id) break;   // listed twice: the first entry serves
+                hsh = (hsh + 1u) & (kHotTab - 1u);
+            }
+        }
+    }
+    for (int k = (int)(threadIdx.x >> lpr_log2); k < nh; k += kHotThreads >> lpr_log2) {
+        const uint32_t id = hot_ids[(size_t)t * kHotRows + k];
+        s_rows[(k << lpr_log2) + li] = ((int64_t)id < R && col_on) ? RowIO<WT>::load_raw(table + (int64_t)id * D + lc)
+                                                                     : RowIO<WT>::zero_raw();
+    }
+    __syncthreads();
+    // ---- the bags
+    const uint32_t gmask = LPR >= 32 ? 0xFFFFFFFFu : ((1u << LPR) - 1u);   // (LPR <= 32 in these classes)
+    const uint32_t below = (1u << li) - 1u;
+    uint32_t* const cold = &s_cold[wv][sub << lpr_log2];
+    uint16_t* const hot = &s_hot[wv][sub << lpr_log2];
+    for (int pass = 0; pass < kHotPasses; ++pass) {
+        const int64_t b = (((int64_t)chunk * kHotPasses + pass) * kHotWaves + wv) * G + sub;
+        if ((((int64_t)chunk * kHotPasses + pass) * kHotWaves + wv) * G >= B) break;   // (the same for all lanes)
+        const bool has_bag = b < B;
+        int64_t start = 0, end = 0;
+        if (has_bag) {   // clamped so that a malformed offsets array can never take a read outside indices[0, nnz)
+            const int64_t bag = (int64_t)t * B + b;
+            start = offsets[bag];
+            end = offsets[bag + 1];
+            start = start < 0 ? 0 : (start > nnz ? nnz : start);
+            end = end < start ? start : (end > nnz ? nnz : end);
+        }
+        const int full_len = (int)((end - start) < (int64_t)0x7FFFFFFF ? (end - start) : (int64_t)0x7FFFFFFF);
+        const bool is_long = full_len > long_bag_min(LPR);   // left to forward_long_bags_kernel
+        const int len = is_long ? 0 : full_len;
+        const int maxlen = wave_max_i32(len);
+        float acc[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] = 0.f;
+        for (int base = 0; base < maxlen; base += LPR) {
+            int32_t my = -1;
+            if (base + li < len) {
+                const int64_t id = indices[start + base + li];
+                if (id >= 0 && id < R) my = (int32_t)id;
+                else atomicOr(err, 1);
+            }
+            int slot = -1;
+            if (my >= 0 && nh > 0) {
+                uint32_t hsh = hot_hash((uint32_t)my);
+                for (;;) {
+                    const uint32_t tid = s_tab_id[hsh];
+                    if (tid == kHotEmpty) break;
+                    if (tid == (uint32_t)my) {
+                        slot = (int)s_tab_slot[hsh];
+                        break;
+                    }
+                    hsh = (hsh + 1u) & (kHotTab - 1u);
+                }
+            }
+            // this lane group's cold ids and hot slots, each list in bag order
+            const bool is_cold = my >= 0 && slot < 0, is_hot = slot >= 0;
+            const uint32_t mc = (uint32_t)(__ballot(is_cold) >> (sub << lpr_log2)) & gmask;
+            const uint32_t mh = (uint32_t)(__ballot(is_hot) >> (sub << lpr_log2)) & gmask;
+            if (is_cold) cold[__popc(mc & below)] = (uint32_t)my;
+            if (is_hot) hot[__popc(mh & below)] = (uint16_t)slot;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const int nc = __popc(mc), nhh = __popc(mh);
+            const int ncmax = wave_max_i32(nc), nhmax = wave_max_i32(nhh);
+            for (int k0 = 0; k0 < ncmax; k0 += U) {
+                raw_t x[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t id = cold[(k0 + u) & (LPR - 1)];
+                    const bool on = (k0 + u) < nc && col_on;
+                    x[u] = on ? RowIO<WT>::load_raw(table + (int64_t)id * D + lc) : RowIO<WT>::zero_raw();
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) RowIO<WT>::accumulate(x[u], acc);
+            }
+            for (int k0 = 0; k0 < nhmax; k0 += 4) {
+                raw_t x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sl = hot[(k0 + u) & (LPR - 1)];
+                    const bool on = (k0 + u) < nhh;
+                    x[u] = on ? s_rows[(sl << lpr_log2) + li] : RowIO<WT>::zero_raw();
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) RowIO<WT>::accumulate(x[u], acc);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the lists are free for the next round
+        }
+        float scale = 1.f;
+        if (MEAN) scale = len > 0 ? 1.f / (float)len : 0.f;
+        if (has_bag && col_on && !is_long) {
+            const int64_t out_elem = b * (int64_t)sumD + d0 + lc;
+#pragma unroll
+            for (int v4 = 0; v4 < V; v4 += 4)
+                store4_from_float(out, out_io, out_elem + v4, acc[v4] * scale, acc[v4 + 1] * scale, acc[v4 + 2] * scale,
+                                  acc[v4 + 3] * scale);
+        }
+    }
+}
+
 // The long bags of the lane-group classes.  A wavefront looks at kLongScan x 64 consecutive bags of one table, 64 at
 // a time with one bag per lane, and walks every bag with more than long_bag_min ids with all of its lanes
 // (forward_bag, as for wide rows).  A kernel of its own: inside the lane-group kernel the second phase pushed the
@@ -293,6 +459,21 @@ static void launch_forward_groups(const tbe_handle* h, const void* tables, const
         const int64_t waves = (int64_t)n * (((int64_t)B + G - 1) / G);
         const dim3 grid((unsigned)((waves + wpb - 1) / wpb));
         const int32_t* list = h->d_fwd_tables + h->fwd_first[c];
+        // with a hot-row list in the handle, and enough bags per table to fill a workgroup's rounds
+        const int64_t bags_per_wg = (int64_t)kHotPasses * kHotWaves * G;
+        const int cpt = (int)(((int64_t)B + bags_per_wg - 1) / bags_per_wg);
+        if (h->d_hot_ids && h->hot_min_workgroups >= 0 && (int64_t)n * cpt >= h->hot_min_workgroups) {
+            const dim3 hgrid((unsigned)((int64_t)n * cpt));
+            if (mean)
+                forward_hot_kernel<WT, TBE_FWD_GROUP_U, true><<<hgrid, kHotThreads, 0, s>>>(
+                    w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io,
+                    h->d_err, h->d_hot_ids, h->d_hot_n, cpt);
+            else
+                forward_hot_kernel<WT, TBE_FWD_GROUP_U, false><<<hgrid, kHotThreads, 0, s>>>(
+                    w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io,
+                    h->d_err, h->d_hot_ids, h->d_hot_n, cpt);
+            continue;
+        }
         if (mean)
             forward_groups_kernel<WT, TBE_FWD_GROUP_U, true><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);

@@ -39,6 +39,7 @@ constexpr int kDenseChunks = 32;            // bag chunks (= partial sums) per d
 #define TBE_FWD_GROUP_MAX_LANES 32
 #endif
 constexpr int kFwdGroupMaxLanes = TBE_FWD_GROUP_MAX_LANES;   // rows of at most this many lanes use one bag per lane group
+constexpr int kHotRows = 256;           // rows per table that the forward may hold in LDS (the handle's hot-row list)
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
@@ -81,6 +82,12 @@ struct tbe_handle {
     // 1..4 = narrow rows (32 / 16 / 8 / <=4 lanes per row), where every lane group of a wavefront takes a bag of its
     // own (2 / 4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables class by class.
     int32_t* d_fwd_tables = nullptr;  // [T]
+    // Hot-row hint: the table-local ids of the rows of every table that had the most lookups in the last backward
+    // call (at most kHotRows each), written by that call's kernels and read by the next forward.  Any contents give
+    // the same forward result; null when the handle has too many tables to keep one.
+    uint32_t* d_hot_ids = nullptr;    // [T][kHotRows]
+    uint32_t* d_hot_n = nullptr;      // [T]
+    int64_t hot_min_workgroups = 256; // the forward stages hot rows in LDS when a width class fills this many workgroups; < 0: never
     int fwd_first[7] = {0, 0, 0, 0, 0, 0, 0};
     int fwd_count[7] = {0, 0, 0, 0, 0, 0, 0};
     // timing

@@ -180,7 +180,7 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
 
 
 def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_sorted: bool = True,
-               index_dtype: torch.dtype = torch.int64, io: str = "f32"):
+               index_dtype: torch.dtype = torch.int64, io: str = "f32", tunables=None):
     tabs = host_tables(cfg)
     flat = flat_from_tables(tabs)
     state_np = np.zeros(cfg.total_rows, dtype=np.float32)
@@ -188,6 +188,8 @@ def run_config(cfg: W.Config, steps: int = 1, state_kind: str = "zeros", check_s
         state_np = W.state_rows(cfg, torch.arange(cfg.total_rows)).numpy()
     state = torch.from_numpy(state_np.copy()).cuda()
     tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    for k, v in (tunables or {}).items():
+        tbe.set_tunable(k, v)
     reports = []
     for step in range(steps):
         idx, off = W.make_batch(cfg, step)
