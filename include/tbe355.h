@@ -115,6 +115,21 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
                                            float momentum_scale, void* tables, float* state, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory or size a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): tbe_backward_rowwise_adagrad_ex with its scratch memory in a fixed array
+ * of TBE_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every GPU the library runs on holds
+ * one copy until the process ends).  Same arguments otherwise, same kernels, bit-identical results.  Allocates
+ * nothing, frees nothing.  A batch that needs more than the array holds - tbe_workspace_bytes(h, B, nnz) >
+ * TBE_STATIC_SCRATCH_BYTES - is refused with TBE_EWORKSPACE before anything is launched.  All calls on one GPU share
+ * that GPU's array, whatever the handle: two such calls that overlap in time on one GPU (different streams or
+ * threads) race, so serialise them; the array keeps the last call's contents, and the kernels clear what they need
+ * cleared themselves.  tbe_debug_sorted does not apply to it. */
+#define TBE_STATIC_SCRATCH_BYTES (64u << 20)
+tbe_status tbe_backward_rowwise_adagrad_static(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                               const void* indices, const void* offsets, tbe_index_dtype index_dtype,
+                                               int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
+                                               float momentum_scale, void* tables, float* state, void* hip_stream);
+
 /* The backward in two calls, so that the part that needs only the ids can leave the critical path.
  * tbe_backward_prepare runs the linearise / sort / run-length steps (Section 2.1: which rows appear in the batch
  * is known from the ids alone) and leaves their result in `workspace`; it may be enqueued on another stream as soon

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("TBE355_LIB", os.path.join(_HERE, "libtbe355.so"))  # override: A/B tests of builds
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, EINDEX, EHIP = range(7)
+STATIC_SCRATCH_BYTES = 64 << 20        # TBE_STATIC_SCRATCH_BYTES
 F32, F16 = 0, 1
 SUM, MEAN = 0, 1
 I64, I32 = 0, 1                       # tbe_index_dtype
@@ -24,7 +25,7 @@ _IO = {torch.float32: IO_F32, torch.float16: IO_F16, torch.bfloat16: IO_BF16}
 
 # every symbol include/tbe355.h declares
 EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "tbe_backward_rowwise_adagrad",
-           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_prepare",
+           "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_rowwise_adagrad_static", "tbe_backward_prepare",
            "tbe_backward_apply_rowwise_adagrad", "tbe_backward_apply_sgd", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
            "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_set_tunable", "tbe_timing_enable",
            "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_calibration_gather", "tbe_status_string"]
@@ -68,6 +69,9 @@ def load_library():
     L.tbe_backward_rowwise_adagrad_ex.restype = ctypes.c_int
     L.tbe_backward_rowwise_adagrad_ex.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int,
                                                   f32, f32, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    L.tbe_backward_rowwise_adagrad_static.restype = ctypes.c_int
+    L.tbe_backward_rowwise_adagrad_static.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, i64, ctypes.c_int,
+                                                      f32, f32, f32, vp, vp, vp]
     L.tbe_backward_prepare.restype = ctypes.c_int
     L.tbe_backward_prepare.argtypes = [vp, vp, vp, ctypes.c_int, i32, i64, vp, ctypes.c_size_t, vp]
     L.tbe_backward_apply_rowwise_adagrad.restype = ctypes.c_int
@@ -247,6 +251,26 @@ class TBE:
             _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(state, torch.float32, "state"),
             _dev_ptr(workspace, torch.uint8, "workspace"), int(workspace.numel()), _stream_ptr(stream))
         _check(st, "tbe_backward_rowwise_adagrad_ex")
+
+    # ---- tbe_backward_rowwise_adagrad_static
+    def backward_rowwise_adagrad_static(self, grad_out: torch.Tensor, indices: torch.Tensor, offsets: torch.Tensor,
+                                        B: int, tables: torch.Tensor, state: torch.Tensor, *, pooling: str = "sum",
+                                        lr: float, eps: float, momentum_scale: float = 1.0,
+                                        stream: Optional[torch.cuda.Stream] = None) -> None:
+        """The backward with the library's own fixed scratch array instead of a caller's workspace."""
+        if tables.numel() != self.total_elems or state.numel() != self.total_rows:
+            raise ValueError("tables / state shape does not match the handle")
+        if grad_out.shape != (B, self.sum_D) or offsets.numel() != self.T * B + 1:
+            raise ValueError("grad_out / offsets shape does not match the handle")
+        if grad_out.dtype not in _IO:
+            raise TypeError(f"grad_out must be float32, float16 or bfloat16, got {grad_out.dtype}")
+        idt = _index_dtype(indices, offsets)
+        st = self._lib.tbe_backward_rowwise_adagrad_static(
+            self._h, _dev_ptr(grad_out, grad_out.dtype, "grad_out"), _IO[grad_out.dtype],
+            _dev_ptr(indices, indices.dtype, "indices"), _dev_ptr(offsets, offsets.dtype, "offsets"), idt, int(B),
+            int(indices.numel()), {"sum": SUM, "mean": MEAN}[pooling], float(lr), float(eps), float(momentum_scale),
+            _dev_ptr(tables, self.torch_dtype, "tables"), _dev_ptr(state, torch.float32, "state"), _stream_ptr(stream))
+        _check(st, "tbe_backward_rowwise_adagrad_static")
 
     # ---- tbe_backward_prepare / tbe_backward_apply_rowwise_adagrad
     def backward_prepare(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, workspace: torch.Tensor,

@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "tbe_internal.h"
@@ -81,6 +82,27 @@ LaunchTimer::LaunchTimer(const tbe_handle* h_, hipStream_t s_, const char* name)
 
 void LaunchTimer::done() {
     if (slot >= 0) (void)hipEventRecord(h->slots[slot].end, s);
+}
+
+// ---- scratch memory for the entry point that allocates nothing ------------------------------------------------------
+// A fixed array in the library's device image, one copy per GPU at that GPU's own address.  In host code the array's
+// name is only a handle for the runtime: its device address is looked up once per device, with that device current,
+// and kept; kernels, copies and fills always get that address, never the name.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[TBE_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, once looked up
+
+// address of `scratch` on the CURRENT device (which is `device`), or nullptr if the runtime cannot give it
+static void* static_scratch_address(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
 }
 
 static int bits_for(uint64_t v) {  // number of bits needed to represent v (>= 1)
@@ -166,6 +188,7 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
         delete h;
         return TBE_EHIP;
     }
+    h->static_scratch = static_scratch_address(h->device);   // (null: the entry point that needs it reports TBE_EHIP)
     const size_t b_doff = align256(4 * (size_t)(T + 1)), b_rb = align256(8 * (size_t)(T + 1)), b_wo = b_rb;
     const size_t b_cls = align256(4 * (size_t)T);
     const bool keep_hot = T <= kMaxSortSegments;
@@ -326,6 +349,19 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
     if (!state) return TBE_EINVAL;
     return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
                          tables, state, workspace, workspace_bytes, hip_stream);
+}
+
+tbe_status tbe_backward_rowwise_adagrad_static(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
+                                               const void* indices, const void* offsets, tbe_index_dtype index_dtype,
+                                               int32_t B, int64_t nnz, tbe_pooling pooling, float lr, float eps,
+                                               float momentum_scale, void* tables, float* state, void* hip_stream) {
+    if (!h || !state) return TBE_EINVAL;
+    const tbe_status st = check_batch(h, B, nnz);
+    if (st != TBE_OK) return st;
+    if (carve(h, nnz).total > (size_t)TBE_STATIC_SCRATCH_BYTES) return TBE_EWORKSPACE;   // beyond the fixed array
+    if (!h->static_scratch) return TBE_EHIP;
+    return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
+                         tables, state, h->static_scratch, (size_t)TBE_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 tbe_status tbe_backward_prepare(const tbe_handle* h, const void* indices, const void* offsets,

@@ -76,6 +76,7 @@ struct tbe_handle {
     int32_t* d_D_off = nullptr;     // [T+1]
     int64_t* d_row_base = nullptr;  // [T+1]
     int64_t* d_w_off = nullptr;     // [T+1]
+    void* static_scratch = nullptr; // device address, on this handle's device, of the library's fixed scratch array
     int32_t* d_err = nullptr;       // sticky invalid-id flag
     const void* d_zero = nullptr;   // 128 bytes of zeros (never written): what a lane with nothing to fetch reads
     // Forward classes: 0, 5, 6 = one wavefront per bag, rows of at most 64 / 128 / 256 sixteen-byte fragments;
