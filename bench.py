@@ -23,25 +23,18 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
-# known size); see the profile summaries under profiles/.  None = not measured for that workload/kernel.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/C4_hbm_traffic.md: FETCH_SIZE x2.0 (calibrated) + WRITE_SIZE x1.0, bytes per step under one timing record
-    # (a record with several launches per step carries their sum).  The counters sit behind the L2: they count what the
-    # L2 asked of the fabric, whether the Infinity Cache or HBM served it.
-    ("C4", "seg_update"): 131.09e9,
-    ("C4", "forward_pool"): 41.52e9,          # the forward launches (32- and 16-lane rows, long-bag scan)
-    ("C4", "seg_long_partial"): 8 * 2.32e9,    # eight launches (one per sub-slice sweep)
-    ("C4", "seg_dense_partial"): 8.52e9,
-    ("C4", "linearize"): 4.48e9,
-    ("C4", "radix_hist"): 3 * 1.12e9,
-    ("C4", "radix_binscan"): 3 * 0.02e9,
-    ("C4", "radix_scatter"): 3 * 4.81e9,
-    ("C4", "rle_count"): 1.06e9,
-    ("C4", "rle_write"): 1.32e9,
-    ("C4", "seg_long_list"): 0.30e9,
-    ("C4", "seg_long_update"): 0.41e9,
-}
+def measured_traffic(workload: str, build: str):
+    """Bytes per step that the byte counters saw, per timing record, from the tracked summary that
+    paper_2508_03854_amd/profile_summary.py wrote for this workload - or None when there is none, or when it was
+    measured on a library built from other sources than the one loaded now (the digest in tbe_build_info())."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if rec.get("build") != build:
+        return None
+    return {k: float(v) for k, v in rec.get("bytes_per_step", {}).items()}
 
 
 def profiler_region(resume: bool) -> None:
@@ -104,6 +97,7 @@ def main():
     ap.add_argument("--pool", type=int, default=4, help="pre-generated batches rotated through")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=16, help="threads of the all-cores oracle baseline (at most the host's cores)")
     ap.add_argument("--rows-scale", type=float, default=1.0,
                     help="shrink every table's row count (profiling aid only; the result is then NOT the named workload)")
     ap.add_argument("--index-dtype", choices=["i64", "i32"], default="i64", help="ids and offsets (i32: *_ex calls)")
@@ -115,6 +109,7 @@ def main():
                     help="replay one captured HIP graph per pooled batch instead of launching every kernel (small, "
                          "launch-bound workloads)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
+    ap.add_argument("--gather-gib", type=int, default=16, help="buffer of the gather calibration in GiB (0 = skip)")
     ap.add_argument("--hot-rows-min-workgroups", type=int, default=None,
                     help="tunable of the forward's on-chip hot-row path (negative: off; default: the library's)")
     args = ap.parse_args()
@@ -126,6 +121,7 @@ def main():
     import torch
     import workloads as W
     from paper_2508_03854_amd import TBE
+    from paper_2508_03854_amd.binding import build_info
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -144,8 +140,11 @@ def main():
     pool = max(1, args.pool)
     batches = W.make_batches(cfg, list(range(pool)), device=dev)
     extended = args.index_dtype != "i64" or args.io != "f32"
-    # the committed counter profiles cover the default call variant of the full-size workload only
-    profiled = not extended and args.rows_scale == 1.0 and args.optimizer == "rowwise_adagrad"
+    # the committed counter profiles cover the default call variant of the full-size workload only, and only the
+    # library build they were measured on
+    default_call = not extended and args.rows_scale == 1.0 and args.optimizer == "rowwise_adagrad" and \
+        args.hot_rows_min_workgroups is None
+    traffic = measured_traffic(cfg.name, build_info()) if default_call else None
     io_t = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.io]
     if args.index_dtype == "i32":
         batches = [(i.to(torch.int32), o.to(torch.int32)) for i, o in batches]
@@ -228,6 +227,30 @@ def main():
         ms = [m for n, m in tbe.timing_read() if n == "calibration_copy"][1:]
         copy_gbps = 2.0 * a_buf.numel() * 4 / (sum(ms) / len(ms) * 1e-3) / 1e9
         del a_buf, b_buf
+    # gather calibration: random slices of known size from a window that fits an L2 (2 MiB per XCD), the Infinity
+    # Cache (32 MiB shared) or neither (2 GiB per XCD), and the same with every slice written back - what this box
+    # delivers for the access pattern of the embedding kernels.  (Slice sizes differ per case only so that the cases
+    # carry different kernel names in a profile; rates do not depend on the size from 128 bytes up.)
+    gather = None
+    if args.gather_gib > 0:
+        g_buf = torch.zeros(args.gather_gib << 30, dtype=torch.uint8, device=dev)
+        sink = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+        per_xcd_big = (args.gather_gib << 30) // 8
+        cases = [("l2_resident_256B", 2 << 20, 256, True, False), ("infinity_cache_512B", 32 << 20, 512, False, False),
+                 ("hbm_1KiB", per_xcd_big, 1024, True, False), ("hbm_128B", per_xcd_big, 128, True, False),
+                 ("hbm_rmw_512B", per_xcd_big, 512, True, True)]
+        gather = {}
+        for name, window, sl, per_xcd, wb in cases:
+            n = int(4e9 // sl)
+            if wb:
+                n = min(n, 8 * (window // sl))
+            tbe.timing_enable(True)
+            for _ in range(3):
+                tbe.calibration_gather(g_buf, window, sl, n, per_xcd=per_xcd, write_back=wb, sink=sink)
+            ms = [m for nm, m in tbe.timing_read() if nm == "calibration_gather"][1:]
+            gather[name] = {"read_GBps": n * sl / (sum(ms) / len(ms) * 1e-3) / 1e9, "slices": n, "slice_bytes": sl,
+                            "window_bytes": window, "per_xcd_windows": per_xcd, "written_back": wb}
+        del g_buf, sink
     tbe.timing_enable(False)
     torch.cuda.synchronize()
     profiler_region(False)
@@ -248,7 +271,7 @@ def main():
                          "min_ms": min(d["all"]), "median_ms": sorted(d["all"])[len(d["all"]) // 2],
                          "alg_bytes_per_launch": bytes_per_launch,
                          "alg_GBps": bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0}
-        measured = MEASURED_TRAFFIC_BYTES.get((cfg.name, name)) if profiled else None
+        measured = traffic.get(name) if traffic else None
         if measured:   # bytes the counters saw per timing record, against what the method must move
             kernels[name]["measured_bytes"] = measured
             kernels[name]["measured_GBps"] = measured / (d["ms"] / prof_steps * 1e-3) / 1e9
@@ -259,14 +282,30 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": dk["alg_GBps"] / HBM_PEAK_GBPS, "avg_launch_ms": dk["avg_ms"],
                 "alg_bytes_per_launch": dk["alg_bytes_per_launch"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant)) if profiled else None}
+                "traffic": (traffic.get(dominant) / max(1.0, dk["launches_per_step"])) if traffic and traffic.get(dominant)
+                else None}
+    if gather:   # the dominant kernel's counter traffic against what the box delivers for gathers beyond the caches
+        roofline["measured_hbm_gather_GBps"] = gather["hbm_1KiB"]["read_GBps"]
+        if roofline["traffic"]:
+            roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9
+            roofline["traffic_frac_of_hbm_gather_rate"] = roofline["traffic_GBps"] / gather["hbm_1KiB"]["read_GBps"]
     fwd_ms = kernels.get("forward_pool", {}).get("ms_per_step", 0.0)
     kernel_ms = sum(k["ms_per_step"] for k in kernels.values())
     step_alg_bytes = sum(alg.get(n, 0.0) * kernels[n]["launches_per_step"] for n in kernels)
     # compulsory bytes of one whole step: the forward set + the backward set (ids are read once more by linearize)
     compulsory = alg["forward_pool"] + alg["seg_update"] + sum(nnz_all[k] for k in used) / len(used) * (8 if args.index_dtype == "i64" else 4)
 
-    counter_bytes = (sum(v for (wl, _), v in MEASURED_TRAFFIC_BYTES.items() if wl == cfg.name) or None) if profiled else None
+    counter_bytes = (sum(traffic.values()) or None) if traffic else None
+    # the whole step against the roofline: compulsory bytes of forward + backward over the measured time per step
+    step_GBps = compulsory / (ms_per_step * 1e-3) / 1e9
+    roofline_step = {"bound": "hbm", "achieved": step_GBps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": step_GBps / HBM_PEAK_GBPS, "compulsory_bytes_per_step": compulsory,
+                     "ms_per_step": ms_per_step}
+    bwd_ms = kernel_ms - fwd_ms
+    roofline_backward = {"bound": "hbm", "achieved": alg["seg_update"] / (bwd_ms * 1e-3) / 1e9 if bwd_ms > 0 else None,
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": alg["seg_update"] / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS if bwd_ms > 0 else None,
+                         "compulsory_bytes": alg["seg_update"], "ms": bwd_ms}
     wb = 4 if cfg.weight_dtype == "f32" else 2
     eb = 4 if args.io == "f32" else 2
     d_bar = cfg.total_elems / max(1, cfg.total_rows)    # row-weighted mean width; ids are spread over rows
@@ -275,6 +314,7 @@ def main():
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1): whole tables, full batch size,
     #      as many leading tables as fit the time budget
     cpu = None
+    cpu_all = None
     if not args.no_cpu_baseline:
         import numpy as np
         import oracle
@@ -318,10 +358,55 @@ def main():
                 nt += 1
             reps = 1
         secs, n = run(nt, min(reps, 50))
+        host_cores = os.cpu_count() or 1
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        shapes = ", ".join(f"{cfg.rows[t]}x{cfg.D[t]}" for t in range(min(nt, 8))) + (" ..." if nt > 8 else "")
         cpu = {"value": n / secs, "unit": "lookups/s", "cores": 1, "kind": "oracle",
-               "sample": f"first {nt} of {cfg.T} tables at full batch size B={cfg.B}, {min(reps, 50)} pass(es), "
-                         f"{n} lookups in {secs:.1f}s, fwd+bwd, single thread",
-               "seconds": secs}
+               "sample": f"first {nt} of {cfg.T} tables (rows x D: {shapes}; {cfg.weight_dtype} weights) at full batch "
+                         f"size B={cfg.B}, {min(reps, 50)} pass(es), {n} lookups in {secs:.1f}s, fwd+bwd, single thread",
+               "seconds": secs, "host_cores": host_cores, "cpu_model": cpu_model}
+        # the same oracle with its loop over tables split over the host's cores: plain threads, one table each per
+        # round (the C oracle runs outside the interpreter lock); tables are independent in both passes
+        from concurrent.futures import ThreadPoolExecutor
+        workers = max(1, min(host_cores, args.cpu_threads, cfg.T))
+        want = min(cfg.T, workers * max(1, int(args.cpu_seconds / max(per_lookup * bounds[1], 1e-9))))
+        want = max(workers, min(want, 2 * workers))
+        want = min(want, cfg.T)
+        doffs = cfg.D_offsets()
+
+        def one_table(t):
+            a = np.ascontiguousarray(flat[woff[t]:woff[t + 1]].view(cfg.rows[t], cfg.D[t]).cpu().numpy())
+            i_np = idx[bounds[t]:bounds[t + 1]].cpu().numpy()
+            o_np = (off[t * cfg.B:(t + 1) * cfg.B + 1] - off[t * cfg.B]).cpu().numpy()
+            g_t = gouts[0][:, doffs[t]:doffs[t + 1]].contiguous().cpu()
+            g_np = g_t.view(torch.int16).numpy().view(np.uint16) if args.io == "bf16" else g_t.numpy()
+            st = np.ascontiguousarray(state[cfg.row_base()[t]:cfg.row_base()[t + 1]].cpu().numpy())
+            return [a], st, g_np, i_np, o_np
+
+        samples = [one_table(t) for t in range(want)]        # copies from HBM: untimed
+
+        def work(sm):
+            tabs, st, g_np, i_np, o_np = sm
+            oracle.forward(tabs, i_np, o_np, cfg.B, cfg.pooling, out_dtype=args.io)
+            oracle.backward_rowwise_adagrad(tabs, None if args.optimizer == "sgd" else st, g_np, i_np, o_np, cfg.B,
+                                            cfg.pooling, cfg.lr, cfg.eps, cfg.c, want_indices=False, grad_dtype=args.io)
+            return int(i_np.size)
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            n_all = sum(ex.map(work, samples))
+        secs_all = time.perf_counter() - t0
+        cpu_all = {"value": n_all / secs_all, "unit": "lookups/s", "cores": workers, "kind": "oracle",
+                   "sample": f"first {want} of {cfg.T} tables at full batch size B={cfg.B}, one pass, one table per thread "
+                             f"at a time, {n_all} lookups in {secs_all:.1f}s, fwd+bwd",
+                   "seconds": secs_all, "host_cores": host_cores, "cpu_model": cpu_model}
 
     result = {
         "metric": "lookups/sec, fused TBE fwd+bwd+rowwise AdaGrad (achieved HBM GB/s in roofline)",
@@ -335,7 +420,13 @@ def main():
                    "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c,
                    "launch": "hip_graph" if args.graph else "eager"},
         "roofline": roofline,
+        "roofline_step": roofline_step,
+        "roofline_backward": roofline_backward,
         "cpu_baseline": cpu,
+        "cpu_baseline_all_cores": cpu_all,
+        "build": build_info(),
+        "profiled_steps": prof_steps,
+        "measured_gather": gather,
         "step_breakdown": {"forward_ms": fwd_ms, "backward_ms": kernel_ms - fwd_ms, "sum_kernel_ms": kernel_ms,
                            "compulsory_bytes_per_step": compulsory,
                            "compulsory_GBps_at_measured_step": compulsory / (ms_per_step * 1e-3) / 1e9,

@@ -258,6 +258,10 @@ tbe_status tbe_calibration_gather(tbe_handle* h, void* buf, size_t buf_bytes, si
 
 const char* tbe_status_string(tbe_status s);
 
+/* "tbe355 gfx950 <digest>": the digest names the sources and build settings this library was compiled from (twelve
+ * hex digits; "unknown" if the build did not supply one).  Profiles record it next to the byte counts they measured. */
+const char* tbe_build_info(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = ["tbe_create", "tbe_destroy", "tbe_workspace_bytes", "tbe_forward", "t
            "tbe_forward_ex", "tbe_backward_rowwise_adagrad_ex", "tbe_backward_rowwise_adagrad_static", "tbe_backward_prepare",
            "tbe_backward_apply_rowwise_adagrad", "tbe_backward_apply_sgd", "tbe_backward_sgd", "tbe_replica_mean", "tbe_lookup_seq",
            "tbe_backward_seq_rowwise_adagrad", "tbe_debug_sorted", "tbe_poll_index_error", "tbe_set_tunable", "tbe_timing_enable",
-           "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_calibration_gather", "tbe_status_string"]
+           "tbe_timing_count", "tbe_timing_read", "tbe_calibration_copy", "tbe_calibration_gather", "tbe_status_string", "tbe_build_info"]
 
 
 class TbeError(RuntimeError):
@@ -107,10 +107,17 @@ def load_library():
     L.tbe_calibration_gather.restype = ctypes.c_int
     L.tbe_calibration_gather.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_size_t, i32, i32, i64, i32, vp,
                                          ctypes.c_size_t, vp]
+    L.tbe_build_info.restype = ctypes.c_char_p
+    L.tbe_build_info.argtypes = []
     L.tbe_status_string.restype = ctypes.c_char_p
     L.tbe_status_string.argtypes = [ctypes.c_int]
     _lib = L
     return L
+
+
+def build_info() -> str:
+    """tbe_build_info(): "tbe355 gfx950 <digest of the sources the loaded library was built from>"."""
+    return load_library().tbe_build_info().decode()
 
 
 def _status_string(s: int) -> str:

@@ -117,6 +117,11 @@ using namespace tbe;
 
 extern "C" {
 
+#ifndef TBE_SOURCE_DIGEST
+#define TBE_SOURCE_DIGEST "unknown"
+#endif
+const char* tbe_build_info(void) { return "tbe355 gfx950 " TBE_SOURCE_DIGEST; }
+
 const char* tbe_status_string(tbe_status s) {
     switch (s) {
         case TBE_OK: return "ok";

@@ -29,53 +29,60 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uint4* __restrict
     }
 }
 
-// A bijection of [0, 2^k): odd multiplications modulo 2^k and right xor-shifts are each invertible, so `count`
-// consecutive inputs (count <= 2^k) give `count` distinct, scattered outputs.
-__device__ __forceinline__ uint64_t scatter_bits(uint64_t x, const int k) {
-    const uint64_t mask = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
+// A bijection of [0, 2^k), k <= 32: odd multiplications modulo 2^k and right xor-shifts are each invertible, so
+// `count` consecutive inputs (count <= 2^k) give `count` distinct, scattered outputs.
+__device__ __forceinline__ uint32_t scatter_bits(uint32_t x, const int k) {
+    const uint32_t mask = (k >= 32) ? 0xFFFFFFFFu : ((1u << k) - 1u);
     const int s1 = k / 2 > 0 ? k / 2 : 1, s2 = k / 3 > 0 ? k / 3 : 1;
     x &= mask;
-    x = (x * 0x9E3779B97F4A7C15ull) & mask;
+    x = (x * 0x9E3779B1u) & mask;
     x ^= x >> s1;
-    x = (x * 0xC2B2AE3D27D4EB4Full) & mask;
+    x = (x * 0x85EBCA6Bu) & mask;
     x ^= x >> s2;
-    x = (x * 0x165667B19E3779F9ull) & mask;
+    x = (x * 0xC2B2AE35u) & mask;
     x ^= x >> s1;
     return x;
 }
 
 // LPR = 16-byte fragments per slice (lanes per slice).  Workgroup id mod 8 = XCD x; XCD x draws the slices
-// i = x, x+8, ... (its eighth of the `gathers`) from window x (per_xcd) or window 0.
+// i = x, x+8, ... (its eighth of the `gathers`) from window x (per_xcd) or window 0.  A wavefront takes 64 slices
+// at a time: every lane works out the place of one of them, then the lane groups fetch them, kU per group in flight.
 template <int LPR, bool RMW>
 __global__ __launch_bounds__(256, 8) void calibration_gather_kernel(uint4* __restrict__ buf, const uint64_t window_frags,
                                                                     const int per_xcd, const int log2_slices,
                                                                     const uint64_t gathers, uint32_t* __restrict__ sink) {
-    constexpr int kU = 8;                 // slices in flight per lane group
     constexpr int G = kWave / LPR;        // lane groups per wavefront
+    constexpr int kU = G >= 8 ? 8 : 4;    // slices in flight per lane group
     const int lane = lane_id();
     const int sub = lane / LPR, frag = lane % LPR;
     const uint32_t xcd = blockIdx.x & 7u;
     const uint64_t per = (gathers + 7u - xcd) / 8u;   // slices of this XCD
-    const uint64_t groups_in_xcd = (uint64_t)(gridDim.x / 8u) * (blockDim.x / kWave) * G;
-    const uint64_t my_group = ((uint64_t)(blockIdx.x / 8u) * (blockDim.x / kWave) + (threadIdx.x >> 6)) * G + sub;
+    const uint64_t waves_in_xcd = (uint64_t)(gridDim.x / 8u) * (blockDim.x / kWave);
+    const uint64_t my_wave = (uint64_t)(blockIdx.x / 8u) * (blockDim.x / kWave) + (threadIdx.x >> 6);
     uint4* win = buf + (per_xcd ? (uint64_t)xcd * window_frags : 0ull);
     uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-    for (uint64_t j0 = my_group; j0 < per; j0 += groups_in_xcd * kU) {
-        uint4 x[kU];
-        uint4* p[kU];
+    for (uint64_t j0 = my_wave * kWave; j0 < per; j0 += waves_in_xcd * kWave) {
+        const uint64_t j = j0 + (uint64_t)lane;                       // this lane's slice
+        // a shared window: read-only gathers of every XCD range over the whole window (each starts elsewhere in the
+        // sequence); written-back ones are numbered globally, so that no two land on one slice
+        const uint32_t place = scatter_bits((uint32_t)(per_xcd ? j : (RMW ? j * 8u + xcd : j + xcd * 0x9E3779u)), log2_slices);
+        const int n = per - j0 < (uint64_t)kWave ? (int)(per - j0) : kWave;
+        for (int k0 = 0; k0 < n; k0 += kU * G) {
+            uint4 x[kU];
+            uint4* p[kU];
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const uint64_t j = j0 + (uint64_t)u * groups_in_xcd;
-            p[u] = win + scatter_bits(per_xcd ? j : j * 8u + xcd, log2_slices) * LPR + frag;
-            x[u] = j < per ? *p[u] : make_uint4(0u, 0u, 0u, 0u);
-        }
+            for (int u = 0; u < kU; ++u) {
+                const int k = k0 + u * G + sub;
+                p[u] = win + (uint64_t)__shfl(place, k & (kWave - 1), kWave) * LPR + frag;
+                x[u] = k < n ? *p[u] : make_uint4(0u, 0u, 0u, 0u);
+            }
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            if (RMW) {
-                const uint64_t j = j0 + (uint64_t)u * groups_in_xcd;
-                if (j < per) *p[u] = make_uint4(x[u].x + 1u, x[u].y, x[u].z, x[u].w);
-            } else {
-                acc.x ^= x[u].x; acc.y ^= x[u].y; acc.z ^= x[u].z; acc.w ^= x[u].w;
+            for (int u = 0; u < kU; ++u) {
+                if (RMW) {
+                    if (k0 + u * G + sub < n) *p[u] = make_uint4(x[u].x + 1u, x[u].y, x[u].z, x[u].w);
+                } else {
+                    acc.x ^= x[u].x; acc.y ^= x[u].y; acc.z ^= x[u].z; acc.w ^= x[u].w;
+                }
             }
         }
     }
@@ -124,6 +131,7 @@ tbe_status tbe_calibration_gather(tbe_handle* h, void* buf, size_t buf_bytes, si
     // written-back slices must be distinct (two lane groups on one slice would race): the place of slice i is a
     // bijection of i, so at most `slices` of them per window
     if (write_back && (per_xcd ? ((uint64_t)gathers + 7u) / 8u : (uint64_t)gathers) > slices) return TBE_ESHAPE;
+    if (slices > (1ull << 32) || (uint64_t)gathers > (1ull << 32)) return TBE_ESHAPE;   // places are 32-bit
     if (gathers == 0) return TBE_OK;
     int log2_slices = 0;
     while ((1ull << log2_slices) < slices) ++log2_slices;
