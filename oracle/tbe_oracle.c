@@ -247,6 +247,10 @@ void oracle_adagrad_row(void* table, int dtype, int64_t r, int32_t D, float* v /
     double sq = 0.0;
     for (int32_t j = 0; j < D; ++j) sq += g[j] * g[j];
     double v_new = (double)(*v) + sq;                       /* step 5: unscaled squared L2 norm accumulates */
+    /* step 6 with v_new == 0 (moments are sums of squares, so this means v == 0 and g == 0): the update term is
+     * eta * 0 / (0 + eps), which is 0 for every eps > 0; its value at eps == 0 is taken to be that limit, so a row
+     * whose gradient is zero keeps its bits for every eps >= 0 and no 0/0 arises */
+    if (v_new == 0.0) return;
     double step = lr / (sqrt(v_new / c) + eps);             /* step 6: c divides the moment inside the root */
     for (int32_t j = 0; j < D; ++j) {
         double w = load_w(table, dtype, r * D + j);

@@ -317,6 +317,48 @@ def test_hand_worked_rows_of_algorithm_1_on_the_gpu():
     assert n == 5
 
 
+def test_zero_gradient_rows_at_zero_moment_with_eps_zero():
+    # rows that appear in the batch with a zero gradient, moment 0, eps = 0: both sides leave them as they are (the
+    # oracle's rule for step 6 at v = 0, g = 0); their neighbours with a nonzero gradient step by lr*sqrt(c)*g/||g||
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import oracle
+    from paper_2508_03854_amd import TBE
+    for dtype, tdt in (("f32", torch.float32), ("f16", torch.float16)):
+        D = 8
+        w0 = (np.arange(5 * D, dtype=np.float32).reshape(5, D) - 17.0) / 64.0
+        tab = w0.astype(np.float16 if dtype == "f16" else np.float32)
+        tbe = TBE([5], [D], dtype)
+        flat = torch.tensor(tab.reshape(-1), dtype=tdt, device="cuda")
+        state = torch.zeros(5, device="cuda")
+        # bags: {0}, {1, 1}, {3}, {4}; gradient rows: zero, zero, nonzero, the negative of itself twice -> cancels for row 1
+        idx = torch.tensor([0, 1, 1, 3, 4], dtype=torch.int64)
+        off = torch.tensor([0, 1, 2, 3, 4, 5], dtype=torch.int64)
+        g = np.zeros((5, D), dtype=np.float32)
+        g[1] = 1.5
+        g[2] = -1.5                       # row 1 is hit by bags 1 and 2: the two gradients cancel exactly
+        g[3] = np.array([3, 0, -4, 0, 0, 0, 0, 0], dtype=np.float32)
+        ws = tbe.alloc_workspace(5, 5)
+        tbe.backward_rowwise_adagrad(torch.tensor(g, device="cuda"), idx.cuda(), off.cuda(), 5, flat, state, ws, lr=0.5,
+                                     eps=0.0, momentum_scale=4.0)
+        torch.cuda.synchronize()
+        assert not tbe.poll_index_error()
+        ref, v = [tab.copy()], np.zeros(5, dtype=np.float32)
+        oracle.backward_rowwise_adagrad(ref, v, g, idx.numpy(), off.numpy(), 5, "sum", 0.5, 0.0, 4.0, want_indices=False)
+        got = flat.cpu().numpy().reshape(5, D)
+        bits = np.uint16 if dtype == "f16" else np.uint32
+        for r in (0, 1, 2, 4):            # zero gradient (rows 0, 1, 4) or not in the batch (row 2): bits kept
+            assert np.array_equal(got[r].view(bits), tab[r].view(bits)), (dtype, r)
+            assert np.array_equal(ref[0][r].view(bits), tab[r].view(bits)), (dtype, r)
+        assert np.isfinite(got).all() and np.isfinite(ref[0]).all()
+        np.testing.assert_allclose(got[3].astype(np.float64), ref[0][3].astype(np.float64),
+                                   rtol=1e-2 if dtype == "f16" else 1e-6, atol=1e-7)
+        np.testing.assert_allclose(got[3].astype(np.float64) - tab[3].astype(np.float64), -0.5 * 2.0 * g[3] / 5.0,
+                                   atol=2e-3 if dtype == "f16" else 1e-6)
+        assert state.cpu().tolist() == [0.0, 0.0, 0.0, 25.0, 0.0] and v.tolist() == [0.0, 0.0, 0.0, 25.0, 0.0]
+        tbe.close()
+
+
 # ---- tables sorted segment by segment on their local ids (fewer key bits than the linearised key needs) ----------
 def test_segmented_sort_shapes(H):
     # 3 x 250 rows: local ids need 8 bits (one radix pass), linearised keys 10 bits (two): the per-table path

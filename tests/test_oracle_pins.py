@@ -176,6 +176,26 @@ def test_prior_moment_closed_form_and_scaling_identity(oracle_mod):
     assert np.abs(a[0] - stale).max() > 1e-4
 
 
+def test_zero_gradient_at_zero_moment_leaves_the_row_for_every_eps(oracle_mod):
+    # Algorithm 1 step 6 at v = 0, g = 0: the update term eta * 0 / (0 + eps) is 0 for every eps > 0, and the limit is
+    # the value taken at eps = 0 (no 0/0): the row and its moment keep their bits.  A nonzero gradient at eps = 0 is
+    # the closed form lr * sqrt(c) * g / ||g|| - finite.
+    w0 = np.array([[0.25, -1.5, 3.0, 0.0]], dtype=np.float32)
+    for eps in (0.0, 1e-8, 1.0):
+        tab, v = w0.copy(), np.zeros(1, dtype=np.float32)
+        oracle_mod.adagrad_row(tab, 0, v, np.zeros(4), 0.01, eps, 2.0)
+        assert np.array_equal(tab.view(np.uint32), w0.view(np.uint32)) and v[0] == 0.0
+    tab, v = w0.copy(), np.zeros(1, dtype=np.float32)
+    g = np.array([3.0, 0.0, -4.0, 0.0])
+    oracle_mod.adagrad_row(tab, 0, v, g, 0.01, 0.0, 4.0)
+    np.testing.assert_allclose(tab[0].astype(np.float64) - w0[0], -0.01 * 2.0 * g / 5.0, atol=1e-7)
+    assert v[0] == 25.0
+    # with a moment already there a zero gradient still changes nothing (step * 0)
+    tab, v = w0.copy(), np.array([2.0], dtype=np.float32)
+    oracle_mod.adagrad_row(tab, 0, v, np.zeros(4), 0.01, 0.0, 1.0)
+    assert np.array_equal(tab.view(np.uint32), w0.view(np.uint32)) and v[0] == 2.0
+
+
 def test_larger_c_means_larger_step(oracle_mod):
     rng = np.random.default_rng(8)
     g = rng.standard_normal(8)
