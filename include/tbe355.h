@@ -137,8 +137,8 @@ tbe_status tbe_backward_rowwise_adagrad_static(const tbe_handle* h, const void* 
  * tbe_backward_apply_rowwise_adagrad then does the per-row reduction and the step (Section 3.2, Algorithm 1 steps
  * 5-6) from grad_out and that workspace.  prepare followed by apply equals tbe_backward_rowwise_adagrad_ex bit for
  * bit.  The caller orders the two (same stream, or an event), passes the same h, offsets, index_dtype, B, nnz and
- * workspace to both, leaves the workspace untouched in between, and calls apply exactly once per prepare (apply
- * consumes counters that prepare cleared).  Argument rules and errors as for the one-call form. */
+ * workspace to both and leaves the workspace untouched in between.  apply may be called again on the same prepared
+ * workspace (every call is one more step on the same batch).  Argument rules and errors as for the one-call form. */
 tbe_status tbe_backward_prepare(const tbe_handle* h, const void* indices, const void* offsets,
                                 tbe_index_dtype index_dtype, int32_t B, int64_t nnz, void* workspace,
                                 size_t workspace_bytes, void* hip_stream);

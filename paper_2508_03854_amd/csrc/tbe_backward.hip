@@ -732,13 +732,30 @@ __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_den
                     const uint4 r = *reinterpret_cast<const uint4*>(&cnt[k * kDenseRows + q]);
                     w[q] = r.x; w[q + 1] = r.y; w[q + 2] = r.z; w[q + 3] = r.w;
                 }
+                // a count of zero times a non-finite gradient element would be NaN, and would reach rows that the bag
+                // does not hold: a fragment with such an element (rare) is added only where the count is not zero
+                const bool odd = !(fabsf(f.x) <= 3.4028234e38f && fabsf(f.y) <= 3.4028234e38f && fabsf(f.z) <= 3.4028234e38f &&
+                                   fabsf(f.w) <= 3.4028234e38f);
+                if (__ballot(odd) == 0ull) {
 #pragma unroll
-                for (int h = 0; h < kDenseRows; ++h) {
-                    const float m = (float)w[h];
-                    acc[h][0] = fmaf(m, f.x, acc[h][0]);
-                    acc[h][1] = fmaf(m, f.y, acc[h][1]);
-                    acc[h][2] = fmaf(m, f.z, acc[h][2]);
-                    acc[h][3] = fmaf(m, f.w, acc[h][3]);
+                    for (int h = 0; h < kDenseRows; ++h) {
+                        const float m = (float)w[h];
+                        acc[h][0] = fmaf(m, f.x, acc[h][0]);
+                        acc[h][1] = fmaf(m, f.y, acc[h][1]);
+                        acc[h][2] = fmaf(m, f.z, acc[h][2]);
+                        acc[h][3] = fmaf(m, f.w, acc[h][3]);
+                    }
+                } else {
+#pragma unroll
+                    for (int h = 0; h < kDenseRows; ++h) {
+                        const float m = (float)w[h];
+                        if (w[h] != 0u) {
+                            acc[h][0] = fmaf(m, f.x, acc[h][0]);
+                            acc[h][1] = fmaf(m, f.y, acc[h][1]);
+                            acc[h][2] = fmaf(m, f.z, acc[h][2]);
+                            acc[h][3] = fmaf(m, f.w, acc[h][3]);
+                        }
+                    }
                 }
             }
         }
@@ -1031,6 +1048,15 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
     }
 }
 
+// Head of every row-update pass: clears what the kernels below count and hand out (hot-row counters, per-table
+// counts, unit tickets), so that the pass can be run again on the same sorted batch.  counters[0], the number of
+// unique rows, belongs to the sort and stays.
+__global__ __launch_bounds__(1024) void seg_reset_kernel(uint32_t* __restrict__ counters, uint32_t* __restrict__ zero,
+                                                         const int zero_words) {
+    for (int i = threadIdx.x; i < zero_words; i += 1024) zero[i] = 0u;
+    if (threadIdx.x >= 1 && threadIdx.x < kCounterWords) counters[threadIdx.x] = 0u;
+}
+
 // the two row-update kernels and the hot-row reduction for one gradient element type
 template <typename GT>
 static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* counters, bool mean, bool narrow,
@@ -1119,6 +1145,8 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     a.counters = counters;
     a.counters_rw = counters;
+    seg_reset_kernel<<<1, 1024, 0, s>>>(counters, reinterpret_cast<uint32_t*>(ws + w.long_tables),
+                                        (int)((w.tickets - w.long_tables) / 4) + kTicketWords);
     if (seq)
         seq_gbase_kernel<<<1, 64, 0, s>>>(IdxView{offsets, idx32}, h->d_D_off, h->T, (int64_t)w.n, grad_elems,
                                           reinterpret_cast<int64_t*>(ws + w.seq_gbase), counters, h->d_err);

@@ -546,13 +546,11 @@ __global__ __launch_bounds__(kRleThreads) void rle_count_kernel(const uint32_t* 
     }
 }
 
-// single block: exclusive scan of the per-tile head counts in place; writes num_unique, the closing
-// seg_start entry, and clears the counters the segment scheduler will bump.
+// single block: exclusive scan of the per-tile head counts in place; writes num_unique and the closing
+// seg_start entry.
 __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ block_counts, const int nblocks,
                                                         const int64_t N, uint32_t* __restrict__ seg_start,
-                                                        uint32_t* __restrict__ counters, uint32_t* __restrict__ zero,
-                                                        const int zero_words) {
-    for (int i = threadIdx.x; i < zero_words; i += 1024) zero[i] = 0u;  // per-table long-row counters, unit tickets
+                                                        uint32_t* __restrict__ counters) {
     __shared__ uint32_t smem[1024 / kWave];
     uint32_t carry = 0;
     for (int base = 0; base < nblocks; base += 4 * 1024) {   // four counts per thread and round: a quarter of the barriers
@@ -572,8 +570,6 @@ __global__ __launch_bounds__(1024) void rle_scan_kernel(uint32_t* __restrict__ b
     if (threadIdx.x == 0) {
         counters[0] = carry;  // num_unique
         seg_start[carry] = (uint32_t)N;
-    } else if (threadIdx.x < kCounterWords) {
-        counters[threadIdx.x] = 0u;  // long-row count, chunk slots
     }
 }
 
@@ -628,9 +624,7 @@ hipError_t launch_run_lengths(const tbe_handle* h, const Workspace& w, char* ws,
     }
     {
         LaunchTimer tm(h, s, "rle_scan");
-        rle_scan_kernel<<<1, 1024, 0, s>>>(counts, w.rle_blocks, N, seg_start, counters,
-                                           reinterpret_cast<uint32_t*>(ws + w.long_tables),
-                                           (int)((w.tickets - w.long_tables) / 4) + kTicketWords);
+        rle_scan_kernel<<<1, 1024, 0, s>>>(counts, w.rle_blocks, N, seg_start, counters);
         tm.done();
     }
     {

@@ -162,6 +162,16 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
             continue
         if cfg.weight_dtype == "f32":
             werr = max(werr, assert_close(gpu_tabs[t][m], tabs[t][m], RTOL_F32, w_scale, f"weights of table {t}"))
+            if same_inputs:
+                # the step itself (Algorithm 1, step 6): w_after - w_before on both sides, to 1e-5 of the row's
+                # largest update plus the rounding of the subtraction (one fp32 ulp of the weights)
+                dw_g = gpu_tabs[t][m].astype(np.float64) - prev_tabs[t][m].astype(np.float64)
+                dw_r = tabs[t][m].astype(np.float64) - prev_tabs[t][m].astype(np.float64)
+                row_max = np.abs(dw_r).max(axis=1, keepdims=True)
+                bound = RTOL_F32 * row_max + 2.0 ** -23 * (np.abs(prev_tabs[t][m]).astype(np.float64) + np.abs(dw_r))
+                bad = np.abs(dw_g - dw_r) > bound
+                assert not bad.any(), (f"updates of table {t}: {int(bad.sum())} elements outside 1e-5 of the row's step; "
+                                       f"worst {np.abs(dw_g - dw_r).max():.3e}")
         else:
             werr = max(werr, assert_close(gpu_tabs[t][m], tabs[t][m], RTOL_F16, w_scale, f"weights of table {t}"))
             if same_inputs:

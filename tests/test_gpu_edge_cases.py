@@ -317,6 +317,40 @@ def test_hand_worked_rows_of_algorithm_1_on_the_gpu():
     assert n == 5
 
 
+def test_ids_repeated_inside_bags_sort_payload_per_segment(H):
+    # several lookups share (row, bag): the pooled sort carries the bag, so such lookups are interchangeable - what
+    # is unique is the multiset of bags per segment, and with the stable order even the sequence: both are compared
+    import oracle
+    from paper_2508_03854_amd import TBE
+    rng = np.random.default_rng(21)
+    cfg = make_cfg([6, 9], [8, 16], B=40, pooling="mean", c=1.0)
+    lens = rng.integers(0, 30, size=2 * 40)
+    off = torch.zeros(81, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.as_tensor(lens, dtype=torch.int64), 0)
+    ids = np.concatenate([rng.integers(0, cfg.rows[t], size=int(lens[t * 40:(t + 1) * 40].sum())) for t in range(2)])
+    idx = torch.as_tensor(ids, dtype=torch.int64)
+    keys, bag_of = oracle.linearize(cfg.rows, ids, off.numpy(), 40)
+    pairs = set(zip(keys.tolist(), bag_of.tolist()))
+    assert len(pairs) < len(ids) // 2                      # most (row, bag) pairs occur more than once
+    tabs = H.host_tables(cfg)
+    flat = H.flat_from_tables(tabs)
+    state_np = np.zeros(cfg.total_rows, dtype=np.float32)
+    state = torch.zeros(cfg.total_rows, device="cuda")
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, idx.numel())
+    gout = torch.randn(cfg.B, cfg.sum_D, generator=torch.Generator().manual_seed(3))
+    H.check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws)     # exact sequence, floats, untouched rows
+    dbg = tbe.debug_sorted(ws, cfg.B, idx.numel())
+    ks_ref, order = oracle.stable_sort(keys)
+    uq, seg = oracle.run_lengths(ks_ref)
+    vs = dbg["vals_sorted"].numpy()
+    for u in range(len(uq)):
+        got = np.sort(vs[seg[u]:seg[u + 1]])
+        want = np.sort(bag_of[order[seg[u]:seg[u + 1]]])
+        assert np.array_equal(got, want), f"segment {u}: bags differ as a multiset"
+    tbe.close()
+
+
 def test_zero_gradient_rows_at_zero_moment_with_eps_zero():
     # rows that appear in the batch with a zero gradient, moment 0, eps = 0: both sides leave them as they are (the
     # oracle's rule for step 6 at v = 0, g = 0); their neighbours with a nonzero gradient step by lr*sqrt(c)*g/||g||
@@ -450,6 +484,79 @@ def test_dense_rows_path(H, dtype, pooling):
     ids = np.concatenate([rng.integers(0, 6, size=n0), ids1, rng.integers(0, 40, size=n2)])
     reps = run_custom(H, cfg, lens, ids, steps=2)
     assert reps[0]["max_seg"] > 20000
+
+
+def test_one_infinite_gradient_element_reaches_only_the_rows_of_its_bag():
+    # dense-row path (the table's gradient block is streamed and added to all dense rows weighted by a count): an
+    # Inf in the gradient of ONE bag must make non-finite exactly the rows that bag holds, as the definition (a sum
+    # over the samples that hit the row, Section 3.2) and the oracle have it - not every dense row of the table
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import oracle
+    from paper_2508_03854_amd import TBE
+    rng = np.random.default_rng(12)
+    B = 32768
+    cfg = make_cfg([6, 300], [64, 64], B=B, pooling="sum", c=1.0, lr=0.01)
+    lens = np.concatenate([rng.integers(2, 5, size=B), rng.integers(0, 2, size=B)])
+    ids0 = rng.integers(0, 6, size=int(lens[:B].sum()))
+    b_inf = 777
+    s0 = int(lens[:b_inf].sum())
+    ids0[s0:s0 + lens[b_inf]] = 2                           # bag 777 of table 0 holds row 2 only
+    ids = np.concatenate([ids0, rng.integers(0, 300, size=int(lens[B:].sum()))])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    gout = torch.randn(B, cfg.sum_D, generator=torch.Generator().manual_seed(1))
+    gout[b_inf, 5] = float("inf")
+    tabs = [W.weight_rows(cfg, t, torch.arange(cfg.rows[t])).numpy() for t in range(2)]
+    flat = torch.from_numpy(np.concatenate([a.reshape(-1) for a in tabs])).cuda()
+    state = torch.zeros(cfg.total_rows, device="cuda")
+    tbe = TBE(cfg.rows, cfg.D, "f32")
+    ws = tbe.alloc_workspace(B, len(ids))
+    tbe.backward_rowwise_adagrad(gout.cuda(), torch.as_tensor(ids).cuda(), torch.as_tensor(off).cuda(), B, flat, state, ws,
+                                 lr=0.01, eps=1e-8)
+    torch.cuda.synchronize()
+    st = np.zeros(cfg.total_rows, dtype=np.float32)
+    oracle.backward_rowwise_adagrad(tabs, st, gout.numpy(), ids, off, B, "sum", 0.01, 1e-8, 1.0, want_indices=False)
+    got = flat.cpu().numpy()[: 6 * 64].reshape(6, 64)
+    fin_got, fin_ref = np.isfinite(got).all(axis=1), np.isfinite(tabs[0]).all(axis=1)
+    assert fin_ref.tolist() == [True, True, False, True, True, True]
+    assert fin_got.tolist() == fin_ref.tolist()
+    np.testing.assert_allclose(got[fin_got], tabs[0][fin_ref], rtol=1e-5, atol=1e-7)
+    sv = state.cpu().numpy()
+    assert np.isfinite(sv[[0, 1, 3, 4, 5]]).all() and not np.isfinite(sv[2])
+    np.testing.assert_allclose(sv[[0, 1, 3, 4, 5]], st[[0, 1, 3, 4, 5]], rtol=1e-5)
+    tbe.close()
+
+
+def test_apply_twice_on_one_prepared_workspace_is_two_steps():
+    # the row-update pass clears its own counters and tickets: run again on the same sorted batch it is one more
+    # step on that batch, equal to two one-call backwards bit for bit (hot rows, dense rows and tickets included)
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_03854_amd import TBE
+    cfg = W.config("C3", T=8, B=16384, rows_scale=0.02, c=2.0)
+    idx, off = (x.cuda() for x in W.make_batch(cfg, 0))
+    gout = W.make_grad_out(cfg, 0).cuda()
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(cfg.B, idx.numel())
+    res = []
+    for split in (False, True):
+        flat = torch.empty(cfg.total_elems, device="cuda")
+        W.fill_weights(cfg, flat)
+        state = torch.zeros(cfg.total_rows, device="cuda")
+        if split:
+            tbe.backward_prepare(idx, off, cfg.B, ws)
+            for _ in range(2):
+                tbe.backward_apply_rowwise_adagrad(gout, off, cfg.B, idx.numel(), flat, state, ws, pooling=cfg.pooling,
+                                                   lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
+        else:
+            for _ in range(2):
+                tbe.backward_rowwise_adagrad(gout, idx, off, cfg.B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr,
+                                             eps=cfg.eps, momentum_scale=cfg.c)
+        torch.cuda.synchronize()
+        res.append((flat, state))
+    assert torch.equal(res[0][0].view(torch.int32), res[1][0].view(torch.int32))
+    assert torch.equal(res[0][1].view(torch.int32), res[1][1].view(torch.int32))
+    tbe.close()
 
 
 def test_sliced_ticketed_and_dense_paths_are_deterministic():

@@ -18,8 +18,11 @@ def _close(got, ref, rtol, scale, what):
     assert (err <= tol).all(), f"{what}: max err {err.max():.3e} (tol {tol[np.argmax(err - tol)]:.3e})"
 
 
-@pytest.mark.parametrize("name", ["C4", "C5", "C3"])
-def test_full_size_sampled_parity(name):
+# the default call (int64 ids, fp32 out / grad_out) of the three largest workloads; the narrow-stream call of the
+# largest (bfloat16 out / grad_out, int32 ids); and the straggler shard with its big tables spread among the small ones
+@pytest.mark.parametrize("name,io,idt", [("C4", "f32", torch.int64), ("C5", "f32", torch.int64), ("C3", "f32", torch.int64),
+                                         ("C4", "bf16", torch.int32), ("C5I", "f32", torch.int64)])
+def test_full_size_sampled_parity(name, io, idt):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import gc
@@ -45,8 +48,11 @@ def test_full_size_sampled_parity(name):
     state = torch.empty(cfg.total_rows, dtype=torch.float32, device=dev)
     W.fill_state(cfg, state, "hash")
     state0 = state.clone()
-    idx, off = W.make_batch(cfg, 0, device=dev)
-    gout = W.make_grad_out(cfg, 0, device=dev)
+    idx, off = W.make_batch(cfg, 0, device=dev)             # int64: kept for the index arithmetic of the checks
+    io_t = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[io]
+    gout = W.make_grad_out(cfg, 0, device=dev).to(io_t)     # both sides see the rounded gradient
+    extended = io != "f32" or idt != torch.int64
+    d_idx, d_off = (idx.to(idt), off.to(idt)) if idt != torch.int64 else (idx, off)
     nnz = idx.numel()
     tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
     ws = tbe.alloc_workspace(B, nnz)
@@ -57,8 +63,12 @@ def test_full_size_sampled_parity(name):
         return (w.to(torch.float16) if f16 else w).numpy()
 
     # ------------------------------------------------------------------ forward, sampled bags
-    out = tbe.forward(flat, idx, off, B, cfg.pooling)
+    if extended:
+        out = tbe.forward_ex(flat, d_idx, d_off, B, cfg.pooling, out_dtype=io_t)
+    else:
+        out = tbe.forward(flat, idx, off, B, cfg.pooling)
     torch.cuda.synchronize()
+    out_rtol = 1e-5 + (0.0 if io == "f32" else (2.0 ** -8 if io == "bf16" else 2.0 ** -11))   # + half an ulp of the format
     assert not tbe.poll_index_error()
     off_cpu = off.cpu().numpy()
     lens = np.diff(off_cpu)
@@ -69,13 +79,17 @@ def test_full_size_sampled_parity(name):
         ids = idx[off_cpu[bag]:off_cpu[bag + 1]].cpu().numpy()
         uniq, inv = np.unique(ids, return_inverse=True)          # compact copy of just the rows this bag touches
         ref = oracle.forward_bag(np.ascontiguousarray(init_rows(t, uniq)), inv.astype(np.int64), 0, len(ids), cfg.pooling)
-        _close(out[b, doff[t]:doff[t + 1]].cpu().numpy(), ref, 1e-5, cfg.w_scale, f"forward bag {bag}")
+        _close(out[b, doff[t]:doff[t + 1]].float().cpu().numpy(), ref, out_rtol, cfg.w_scale, f"forward bag {bag}")
     print("forward: %d sampled bags ok" % len(bags), flush=True)
     del out
 
     # ------------------------------------------------------------------ backward
-    tbe.backward_rowwise_adagrad(gout, idx, off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
-                                 momentum_scale=cfg.c)
+    if extended:
+        tbe.backward_rowwise_adagrad_ex(gout, d_idx, d_off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
+                                        momentum_scale=cfg.c)
+    else:
+        tbe.backward_rowwise_adagrad(gout, idx, off, B, flat, state, ws, pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps,
+                                     momentum_scale=cfg.c)
     torch.cuda.synchronize()
     assert not tbe.poll_index_error()
 
@@ -135,7 +149,7 @@ def test_full_size_sampled_parity(name):
             picks.add(int(u_ids[j]))
         ids_np = ids_t.cpu().numpy()
         off_t = off_cpu[t * B:(t + 1) * B + 1] - off_cpu[t * B]
-        g_block = np.ascontiguousarray(gout[:, doff[t]:doff[t + 1]].cpu().numpy())
+        g_block = np.ascontiguousarray(gout[:, doff[t]:doff[t + 1]].float().cpu().numpy())   # (16-bit values are exact in fp32)
         for r in sorted(picks):
             g, hits = oracle.row_gradient_by_scan(0, r, D, 0, g_block, ids_np, off_t, B, cfg.pooling)
             assert hits == int(cnt[(u_ids == r).nonzero()[0, 0]])
@@ -152,6 +166,6 @@ def test_full_size_sampled_parity(name):
         print("table %d (R=%d, D=%d): %d sampled rows ok" % (t, R, D, len(picks)), flush=True)
     print("all %d tables: the rows that changed are exactly the rows of the batch" % T, flush=True)
     tbe.close()
-    del flat, state, state0, idx, off, gout, ws, dbg, ks, vs, uq, ss, cur, moved, touched
+    del flat, state, state0, idx, off, d_idx, d_off, gout, ws, dbg, ks, vs, uq, ss, cur, moved, touched
     gc.collect()
     torch.cuda.empty_cache()

@@ -55,7 +55,8 @@ def test_random_shape(H, seed):
     from paper_2508_03854_amd import TBE
     k = draw_case(seed)
     cfg = W.Config("rand", list(k["rows"]), list(k["D"]), k["dtype"], k["B"], k["pooling"], ("fixed", 1), ("uniform",))
-    cfg.c, cfg.lr, cfg.eps = k["c"], 0.05, 1e-8
+    # lr = 0.01 as in the workloads: the same one-ulp mismatch budget (2e-3) as every other fp16 case then applies
+    cfg.c, cfg.lr, cfg.eps = k["c"], 0.01, 1e-8
     off = torch.zeros(len(k["lens"]) + 1, dtype=torch.int64)
     off[1:] = torch.cumsum(torch.as_tensor(k["lens"], dtype=torch.int64), 0)
     idx = torch.as_tensor(k["ids"], dtype=torch.int64)
@@ -69,6 +70,6 @@ def test_random_shape(H, seed):
     for s in range(2):
         gout = torch.randn(cfg.B, cfg.sum_D, generator=g, dtype=torch.float32)
         rep = H.check_step(cfg, tbe, flat, state, tabs, state_np, idx, off, gout, ws, same_inputs=(s == 0),
-                           index_dtype=k["idt"], io=k["io"], ulp_rate=3e-2)   # lr = 0.05: updates as large as the weights
+                           index_dtype=k["idt"], io=k["io"])
     print(seed, cfg.T, cfg.B, k["dtype"], k["io"], k["pooling"], idx.numel(), rep, flush=True)
     tbe.close()

@@ -60,9 +60,11 @@ def run_seq(H, cfg, io="f32", idt=torch.int64, steps=2):
         # integer by-products: the stable sort of (row key, position)
         base = np.asarray(cfg.row_base())
         keys = np.concatenate([idx.numpy()[toff[t]:toff[t + 1]] + base[t] for t in range(cfg.T)])
-        order = np.argsort(keys, kind="stable")
-        assert np.array_equal(dbg["keys_sorted"].numpy(), keys[order])
+        ks_ref, order = oracle.stable_sort(keys)              # the oracle's sort (pinned against the library's on the CPU)
+        assert np.array_equal(dbg["keys_sorted"].numpy(), ks_ref)
         assert np.array_equal(dbg["vals_sorted"].numpy(), order)
+        uq_ref, seg_ref = oracle.run_lengths(ks_ref)
+        assert np.array_equal(dbg["unique_rows"].numpy(), uq_ref) and np.array_equal(dbg["seg_start"].numpy(), seg_ref)
         touched = np.zeros(cfg.total_rows, dtype=bool)
         touched[dbg["unique_rows"].numpy()] = True
         assert touched.sum() == U
