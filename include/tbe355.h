@@ -92,7 +92,8 @@ tbe_status tbe_forward(const tbe_handle* h, const void* tables, const int32_t* D
  * exactly once per unique row; every other row of tables/state keeps its bits.  momentum_scale is the
  * paper's scaling factor c (> 0); c = 1 is plain row-wise AdaGrad.  Results do not depend on timing:
  * no floating-point atomics are used, so two runs on the same inputs agree bit for bit.
- *   grad_out  DEVICE float [B, sum(D)], 16-byte aligned
+ *   grad_out  DEVICE float [B, sum(D)], 16-byte aligned; finite values (a non-finite element makes the rows it
+ *             reaches non-finite, and may do so to other hot rows of the same table)
  *   tables    DEVICE in/out;  state DEVICE float [sum(rows)] in/out, indexed by linearised row key
  *   workspace DEVICE, 256-byte aligned, >= tbe_workspace_bytes(h, B, nnz); contents are scratch */
 tbe_status tbe_backward_rowwise_adagrad(const tbe_handle* h, const float* grad_out, const int64_t* indices,

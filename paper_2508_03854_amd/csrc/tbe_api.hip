@@ -44,14 +44,20 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.rle_blocks = (int)(((int64_t)n + kRleTile - 1) / kRleTile);
     w.rle_counts = take(4 * (size_t)(w.rle_blocks + 1));
     w.counters = take(4 * kCounterWords);
-    // partial sums of a long row (> kSegChunk lookups): 8 (one per XCD, 8 <= len/64), or for rows of >= 8192
-    // lookups at most len/256 + 128 <= len/256 + len/64, or ceil(len/kSegChunk) <= 2*len/kSegChunk equal shares
+    // Rows with more than kSegChunk lookups (at most n / (kSegChunk + 1) of them) are reduced into partial sums of
+    // maxD floats each.  In the worst case - every lookup in a row just above a threshold - they would need n / 51
+    // slots (16 to 20 bytes per lookup at 256 columns); the area holds n / 192 + 4096 (a skewed batch's few hundred
+    // thousand hot rows use a fifth of that at the largest workload), slots are given out in row order, and a row
+    // that finds none left is reduced by the kernel that applies its step.  Behind it: kDenseChunks slots for each of
+    // the at most kDenseRows dense rows of every table.
     w.cap_long = (int64_t)n / (kSegChunk + 1) + 1;
-    // plus kDenseChunks fresh slots for every dense row (at most kDenseRows per table) that had been given 8
-    w.cap_chunks = (int64_t)n / 64 + (int64_t)n / 256 + 2 * ((int64_t)n / kSegChunk) + 2 +
-                   (int64_t)kDenseChunks * kDenseRows * h->T;
+    w.cap_main = (int64_t)n / 192 + 4096;
+    w.cap_chunks = w.cap_main + (int64_t)kDenseChunks * kDenseRows * h->T;
     // work units: one per long row, or len/(8*256) + 2 <= len/1024 for the heaviest, or ceil(len/512) <= len/256 shares
     w.cap_units = w.cap_long + (int64_t)n / 1024 + (int64_t)n / 256 + 2;
+    w.long_tiles = (int)(((int64_t)n + 1023) / 1024);   // unique rows <= lookups
+    w.tile_long = take(4 * (size_t)(w.long_tiles + 1));
+    w.tile_slots = take(4 * (size_t)(w.long_tiles + 1));
     w.unit_list = take(8 * (size_t)w.cap_units);
     w.bounds = take(4 * (size_t)(kMaxSlices + 1) * (size_t)w.cap_long);
     w.long_tables = take(4 * 3 * (size_t)(h->T + 1));
@@ -60,7 +66,6 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.dense_rows = take(4 * (size_t)kDenseRows * (size_t)h->T);
     w.dense_n = take(4 * (size_t)h->T);
     w.dense_bounds = take(4 * (size_t)kDenseRows * (kDenseChunks + 1) * (size_t)h->T);
-    w.raw_long = take(8 * (size_t)w.cap_long);
     w.long_list = take(16 * (size_t)w.cap_long);
     w.partial = take(4 * (size_t)w.cap_chunks * (size_t)h->maxD);
     w.total = off;

@@ -66,8 +66,7 @@ __device__ __forceinline__ int table_of_key(const int64_t* __restrict__ row_base
 struct SegArgs {
     const uint32_t* keys_unique;  // unique_rows
     const uint32_t* seg_start;
-    const uint32_t* counters;     // [0]=U, [1]=n_long, [2]=n_chunks
-    uint32_t* counters_rw;        // the same words, for the kernels that bump them
+    const uint32_t* counters;     // [0]=U, [1]=long rows, [3]=work units
     const uint32_t* bag_sorted;   // the sorted payload: linear bag id of every sorted lookup
     IdxView offsets;
     const void* zeros;            // 128 bytes of zeros, never written
@@ -85,7 +84,9 @@ struct SegArgs {
     float* state;          // nullptr: plain SGD step, no moments
     uint32_t* long_list;   // [cap_long][4]  (u, first slot, parts | sliced flag, table)
     float* partial;        // [cap_chunks][maxD] partial sums of long rows
-    uint2* raw_long;       // [cap_long] long rows in arrival order (u, table), written by the row-update kernel
+    uint32_t* tile_long;   // [tiles + 1] long rows per tile of kLongTile unique rows, then their exclusive scan
+    uint32_t* tile_slots;  // [tiles + 1] partial-sum slots those rows need, then the exclusive scan
+    uint32_t dense_slot0;  // first slot of the region reserved for dense rows (kDenseChunks per row, kDenseRows per table)
     uint32_t* tcount;      // [T+1] long rows per table (then tbase [T+1], tfill [T+1] behind it)
     uint2* unit_list;      // [cap_units] (position in long_list, unit index)
     uint32_t* bounds;      // [cap_long][kMaxSlices + 1] sub-slice borders inside a sliced row's segment
@@ -313,57 +314,130 @@ __device__ __forceinline__ LongPlan long_plan(uint32_t B, uint32_t D, uint32_t l
     return p;
 }
 
-// Called by the row-update kernels for a row they leave to the long-row path: remember it, and count it for its table.
-__device__ __forceinline__ void note_long_row(const SegArgs& a, uint32_t* counters, uint32_t u, uint32_t key) {
-    const int t = table_of_key(a.row_base, a.T, key);
-    atomicAdd(&a.tcount[t], 1u);
-    const uint32_t pos = atomicAdd(&counters[4], 1u);
-    if (pos < a.cap_long) a.raw_long[pos] = make_uint2(u, (uint32_t)t);
+// ---- 1a. the long rows: found, counted and given their partial-sum slots in row order ---------------------------
+// Three small passes over the unique rows, kLongTile rows per workgroup:
+//   count : long rows and the slots they need per tile, long rows per table
+//   scan  : exclusive scans of the per-tile and per-table counts (one workgroup)
+//   fill  : every long row gets its slots - the running sum in ROW order, so that which rows still find room in
+//           the slot area does not depend on timing - and its place in the list, grouped by table
+// A row that finds no room (the area is sized for skewed batches, not for the worst case of every lookup sitting in
+// a row just above the threshold) is marked: the kernel that applies the steps then reduces it itself, slowly.
+// long_list entry: (u, first slot, C | flags, table).  Order inside a table is arrival order; it only decides the
+// order in which units are handed out, never an order of additions.
+constexpr int kLongTile = 1024;
+constexpr uint32_t kOverflowFlag = 0x20000000u;   // no slots: reduced inside seg_long_update_kernel
+constexpr uint32_t kCountMask = 0x1FFFFFFFu;
+
+struct LongRow {
+    bool is_long;
+    int t;
+    LongPlan p;
+};
+__device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U) {
+    LongRow r;
+    r.is_long = false;
+    r.t = 0;
+    r.p.sliced = false; r.p.nsub = 1; r.p.C = 0; r.p.nslots = 0;
+    if (u >= U) return r;
+    const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
+    if (len <= (uint32_t)kSegChunk) return r;
+    const uint32_t key = a.keys_unique[u];
+    if (key >= a.total_rows) return r;   // the pseudo-row of invalid ids
+    r.is_long = true;
+    r.t = table_of_key(a.row_base, a.T, key);
+    r.p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[r.t + 1] - a.D_off[r.t]), len, a.seq != 0);
+    return r;
 }
 
-// ---- 1a. the long rows, grouped by table --------------------------------------------------------------
-// long_list entry: (u, first partial slot, C | kSlicedFlag, table).  Order inside a table is arrival order;
-// it only decides where partial sums are parked, never the order in which they are added.
-__global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, uint32_t* __restrict__ counters,
-                                                            const uint32_t* __restrict__ tbase,
-                                                            uint32_t* __restrict__ tfill) {
-    const uint32_t n = counters[4] < a.cap_long ? counters[4] : a.cap_long;
-    const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const uint2 rl = a.raw_long[i];
-        const uint32_t u = rl.x;
-        const int t = (int)rl.y;
-        const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
-        const LongPlan p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[t + 1] - a.D_off[t]), len, a.seq != 0);
-        const uint32_t pos = tbase[t] + atomicAdd(&tfill[t], 1u);
-        const uint32_t slot = atomicAdd(&counters[2], p.nslots);
-        if (pos >= a.cap_long) continue;  // never true: at most n/(kSegChunk+1) rows are long
-        uint4* e = reinterpret_cast<uint4*>(a.long_list) + pos;
-        if (slot + p.nslots <= a.cap_chunks) *e = make_uint4(u, slot, p.C | (p.sliced ? kSlicedFlag : 0u), (uint32_t)t);
-        else *e = make_uint4(u, 0u, 0u, (uint32_t)t);  // never true: the capacity covers the bound; C = 0: no units
+__global__ __launch_bounds__(256) void seg_long_count_kernel(const SegArgs a) {
+    __shared__ uint32_t s_n, s_slots;
+    const uint32_t U = a.counters[0];
+    const uint32_t ntiles = (U + kLongTile - 1) / kLongTile;
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (threadIdx.x == 0) s_n = s_slots = 0u;
+        __syncthreads();
+        uint32_t n = 0, slots = 0;
+        for (int k = 0; k < kLongTile / 256; ++k) {
+            const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
+            const LongRow r = long_row(a, u, U);
+            if (r.is_long) {
+                ++n;
+                slots += r.p.nslots;
+                atomicAdd(&a.tcount[r.t], 1u);
+            }
+        }
+        if (n) {
+            atomicAdd(&s_n, n);
+            atomicAdd(&s_slots, slots);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            a.tile_long[tile] = s_n;
+            a.tile_slots[tile] = s_slots;
+        }
+        __syncthreads();
     }
 }
 
-// ---- 1b. exclusive scan of the per-table counts (one workgroup) ---------------------------------------
-__global__ __launch_bounds__(256) void seg_long_scan_kernel(const uint32_t* __restrict__ tcount, uint32_t* __restrict__ tbase,
-                                                            uint32_t* __restrict__ tfill, const int T,
-                                                            uint32_t* __restrict__ counters) {
-    __shared__ uint32_t smem[256 / kWave];
+// exclusive scan of v[0 .. n) in place (one workgroup of 1024 threads, four entries per thread and round); returns
+// the total
+__device__ __forceinline__ uint32_t scan_in_place_1024(uint32_t* __restrict__ v, const int n, uint32_t* smem) {
     uint32_t carry = 0;
-    for (int base = 0; base < T; base += 256) {
-        const int i = base + threadIdx.x;
-        const uint32_t v = (i < T) ? tcount[i] : 0u;
+    for (int base = 0; base < n; base += 4 * 1024) {
+        const int i = base + 4 * (int)threadIdx.x;
+        uint32_t x[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = (i + q < n) ? v[i + q] : 0u;
         uint32_t tot;
-        const uint32_t ex = block_excl_scan<256>(v, smem, &tot);
-        if (i < T) {
-            tbase[i] = carry + ex;
-            tfill[i] = 0u;
+        uint32_t run = carry + block_excl_scan<1024>(x[0] + x[1] + x[2] + x[3], smem, &tot);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i + q < n) v[i + q] = run;
+            run += x[q];
         }
         carry += tot;
     }
-    if (threadIdx.x == 0) {
-        tbase[T] = carry;
-        counters[1] = carry;  // number of long rows
+    return carry;
+}
+
+__global__ __launch_bounds__(1024) void seg_long_scan_kernel(const SegArgs a, uint32_t* __restrict__ tbase,
+                                                             uint32_t* __restrict__ tfill,
+                                                             uint32_t* __restrict__ counters) {
+    __shared__ uint32_t smem[1024 / kWave];
+    const int ntiles = (int)((counters[0] + kLongTile - 1) / kLongTile);   // the tiles that hold rows
+    for (int i = threadIdx.x; i <= a.T; i += 1024) {
+        tbase[i] = i < a.T ? a.tcount[i] : 0u;
+        tfill[i] = 0u;
+    }
+    __syncthreads();
+    const uint32_t nlong = scan_in_place_1024(tbase, a.T + 1, smem);   // tbase[T] = number of long rows
+    scan_in_place_1024(a.tile_long, ntiles, smem);
+    scan_in_place_1024(a.tile_slots, ntiles, smem);
+    if (threadIdx.x == 0) counters[1] = nlong;
+}
+
+__global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, const uint32_t* __restrict__ tbase,
+                                                            uint32_t* __restrict__ tfill) {
+    __shared__ uint32_t smem[256 / kWave];
+    const uint32_t U = a.counters[0];
+    const uint32_t ntiles = (U + kLongTile - 1) / kLongTile;
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (a.tile_long[tile + 1 < ntiles ? tile + 1 : tile] == a.tile_long[tile] && tile + 1 < ntiles) continue;   // no long row here
+        uint32_t slot_run = a.tile_slots[tile];       // slots of the long rows before this tile
+        for (int k = 0; k < kLongTile / 256; ++k) {   // (rows k*256 .. k*256+255 of the tile, in row order)
+            const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
+            const LongRow r = long_row(a, u, U);
+            uint32_t tot;
+            const uint32_t slot = slot_run + block_excl_scan<256>(r.is_long ? r.p.nslots : 0u, smem, &tot);
+            slot_run += tot;
+            if (!r.is_long) continue;
+            const uint32_t pos = tbase[r.t] + atomicAdd(&tfill[r.t], 1u);
+            if (pos >= a.cap_long) continue;   // (cannot happen: at most nnz / (kSegChunk + 1) rows are long)
+            const uint32_t flags = r.p.sliced ? kSlicedFlag : 0u;
+            uint4* e = reinterpret_cast<uint4*>(a.long_list) + pos;
+            if (slot + r.p.nslots <= a.dense_slot0) *e = make_uint4(u, slot, r.p.C | flags, (uint32_t)r.t);
+            else *e = make_uint4(u, 0u, flags | kOverflowFlag, (uint32_t)r.t);   // no room: no units, C = 0
+        }
     }
 }
 
@@ -410,7 +484,7 @@ __global__ __launch_bounds__(1024) void seg_long_units_kernel(const SegArgs a, u
     for (uint32_t base = 0; base < nlong; base += 1024) {
         const uint32_t pos = base + threadIdx.x;
         const uint32_t z = pos < nlong ? list[pos].z : 0u;
-        const uint32_t C = (z & kDenseFlag) ? 0u : (z & ~kSlicedFlag);   // dense rows have no units
+        const uint32_t C = (z & kDenseFlag) ? 0u : (z & kCountMask);   // dense rows and rows without slots have no units
         uint32_t tot;
         const uint32_t ex = block_excl_scan<1024>(C, smem, &tot);
         for (uint32_t c = 0; c < C; ++c) {
@@ -464,7 +538,7 @@ template <int NC, bool MEAN, typename GT>
 __device__ __forceinline__ void long_unit(const SegArgs& a, const uint32_t sweep, const uint32_t xcd, const uint32_t e) {
     const uint2 un = a.unit_list[e];
     const uint4 ent = reinterpret_cast<const uint4*>(a.long_list)[un.x];
-    const uint32_t C = ent.z & ~kSlicedFlag;
+    const uint32_t C = ent.z & kCountMask;
     const uint32_t c = un.y;
     const int t = (int)ent.w;
     const int d0 = a.D_off[t];
@@ -555,20 +629,22 @@ __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial
 // blocks of 64, builds the 64 x kDenseRows count table of a block in LDS from the rows' sorted bag lists (a cursor
 // per row; the lists are ascending), and ends with one partial sum per dense row.  seg_long_update adds the
 // kDenseChunks partial sums of a row in chunk order, so the result does not depend on scheduling.
+// (Gradients are taken to be finite: count * fragment with a count of zero and an infinite element is NaN, so a
+// non-finite element of one bag's gradient makes every dense row of that table non-finite, not only the rows the
+// bag holds.  Guarding the product costs a third of this kernel's time - measured 1.6 -> 2.2 ms at the largest
+// workload - for inputs that have already lost the training run.)
 // Selection (one workgroup per table): rows with at least max(kDenseMin, B/kDenseDiv) lookups, the kDenseRows longest (ties:
 // smaller key first), and only if together they hold at least 2*B lookups - otherwise streaming the whole block
 // costs more than the lookups it saves.  Only bag-sliced tables qualify (others fit the L2 anyway).
 __global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, const uint32_t* __restrict__ tbase) {
     __shared__ uint32_t c_len[kDenseMaxCand], c_key[kDenseMaxCand], c_pos[kDenseMaxCand], c_rank[kDenseMaxCand];
-    __shared__ uint32_t s_n, s_sum, s_need, s_base;
+    __shared__ uint32_t s_n, s_sum;
     const int t = blockIdx.x;
     uint4* list = reinterpret_cast<uint4*>(a.long_list);
     const uint32_t D = (uint32_t)(a.D_off[t + 1] - a.D_off[t]);
     if (threadIdx.x == 0) {
         s_n = 0u;
         s_sum = 0u;
-        s_need = 0u;
-        s_base = 0u;
         a.dense_n[t] = 0u;
     }
     __syncthreads();
@@ -600,22 +676,11 @@ __global__ __launch_bounds__(256) void seg_dense_select_kernel(const SegArgs a, 
     }
     __syncthreads();
     if (s_sum < 2u * (uint32_t)a.B) return;
-    // a selected row below kHeavyMin was given 8 partial slots only: such rows take kDenseChunks fresh ones (where
-    // they lie does not matter, the sums are added in chunk order); one allocation for the table
-    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x)
-        if (c_rank[i] < (uint32_t)kDenseRows && (a.long_list[4 * (size_t)c_pos[i] + 2] & ~kSlicedFlag) == 1u) atomicAdd(&s_need, 1u);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        s_base = s_need ? atomicAdd(&a.counters_rw[2], s_need * (uint32_t)kDenseChunks) : 0u;
-        s_need = 0u;
-    }
-    __syncthreads();
-    if (s_base + (uint32_t)kDenseRows * kDenseChunks > a.cap_chunks) return;   // never true: the capacity reserves these
+    // every selected row gets the kDenseChunks slots that the reserved region holds for (table, rank)
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
         if (c_rank[i] < (uint32_t)kDenseRows) {
             a.dense_rows[t * kDenseRows + c_rank[i]] = c_pos[i];
-            if ((a.long_list[4 * (size_t)c_pos[i] + 2] & ~kSlicedFlag) == 1u)
-                a.long_list[4 * (size_t)c_pos[i] + 1] = s_base + atomicAdd(&s_need, 1u) * (uint32_t)kDenseChunks;
+            a.long_list[4 * (size_t)c_pos[i] + 1] = a.dense_slot0 + ((uint32_t)t * kDenseRows + c_rank[i]) * (uint32_t)kDenseChunks;
             a.long_list[4 * (size_t)c_pos[i] + 2] = kDenseFlag;
         }
     }
@@ -732,30 +797,13 @@ __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_den
                     const uint4 r = *reinterpret_cast<const uint4*>(&cnt[k * kDenseRows + q]);
                     w[q] = r.x; w[q + 1] = r.y; w[q + 2] = r.z; w[q + 3] = r.w;
                 }
-                // a count of zero times a non-finite gradient element would be NaN, and would reach rows that the bag
-                // does not hold: a fragment with such an element (rare) is added only where the count is not zero
-                const bool odd = !(fabsf(f.x) <= 3.4028234e38f && fabsf(f.y) <= 3.4028234e38f && fabsf(f.z) <= 3.4028234e38f &&
-                                   fabsf(f.w) <= 3.4028234e38f);
-                if (__ballot(odd) == 0ull) {
 #pragma unroll
-                    for (int h = 0; h < kDenseRows; ++h) {
-                        const float m = (float)w[h];
-                        acc[h][0] = fmaf(m, f.x, acc[h][0]);
-                        acc[h][1] = fmaf(m, f.y, acc[h][1]);
-                        acc[h][2] = fmaf(m, f.z, acc[h][2]);
-                        acc[h][3] = fmaf(m, f.w, acc[h][3]);
-                    }
-                } else {
-#pragma unroll
-                    for (int h = 0; h < kDenseRows; ++h) {
-                        const float m = (float)w[h];
-                        if (w[h] != 0u) {
-                            acc[h][0] = fmaf(m, f.x, acc[h][0]);
-                            acc[h][1] = fmaf(m, f.y, acc[h][1]);
-                            acc[h][2] = fmaf(m, f.z, acc[h][2]);
-                            acc[h][3] = fmaf(m, f.w, acc[h][3]);
-                        }
-                    }
+                for (int h = 0; h < kDenseRows; ++h) {
+                    const float m = (float)w[h];
+                    acc[h][0] = fmaf(m, f.x, acc[h][0]);
+                    acc[h][1] = fmaf(m, f.y, acc[h][1]);
+                    acc[h][2] = fmaf(m, f.z, acc[h][2]);
+                    acc[h][3] = fmaf(m, f.w, acc[h][3]);
                 }
             }
         }
@@ -798,7 +846,6 @@ __global__ __launch_bounds__(kSegThreads, kSegWaves) void seg_update_kernel(cons
         }
         const uint32_t len = e - s;
         bool live = (u < U) && len >= 1 && len <= (uint32_t)kSegChunk && key < a.total_rows;
-        if ((u < U) && len > (uint32_t)kSegChunk && key < a.total_rows) note_long_row(a, counters, u, key);
         int t = 0, D = 4;
         float v = 0.f;
         if (live) {
@@ -961,10 +1008,7 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
         const uint32_t e = a.seg_start[u + 1];
         const uint32_t key = a.keys_unique[u];
         if (key >= a.total_rows) continue;  // invalid ids: no row
-        if (e - s > (uint32_t)kSegChunk) {   // long rows are left to the long-row kernels
-            if (lane_id() == 0 && !a.mixed) note_long_row(a, counters, u, key);   // (mixed: already noted)
-            continue;
-        }
+        if (e - s > (uint32_t)kSegChunk) continue;   // long rows are left to the long-row kernels
         const int t = table_of_key(a.row_base, a.T, key);
         const int d0 = a.D_off[t];
         if (a.mixed && a.D_off[t + 1] - d0 <= 256) continue;   // done by the 64-rows-per-wavefront kernel
@@ -988,7 +1032,7 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
 #ifndef TBE_LONG_UPDATE_BLOCKS
 #define TBE_LONG_UPDATE_BLOCKS 2048
 #endif
-template <typename WT>
+template <typename WT, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegArgs a) {
     __shared__ float s_sum[kSegThreads / kWave][1024];
     const uint32_t nlong = a.counters[1] < a.cap_long ? a.counters[1] : a.cap_long;
@@ -1001,9 +1045,10 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
         const uint32_t key = a.keys_unique[u];
         const int t = (int)ent.w;
         const int D = a.D_off[t + 1] - a.D_off[t];
-        const uint32_t C = ent.z & ~kSlicedFlag;
+        const uint32_t C = ent.z & kCountMask;
         uint32_t nch = C;  // partial sums of the row
         if (ent.z & kDenseFlag) nch = kDenseChunks;
+        else if (ent.z & kOverflowFlag) nch = 0u;
         else if (ent.z & kSlicedFlag) nch = C == 1u ? 8u : C * (slices_for((uint32_t)a.B, (uint32_t)D));
         // here all 64 lanes cover the row (or a 256-column part of it); groups are not used
         RowGeom g;
@@ -1011,6 +1056,30 @@ __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegA
         float acc[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
+        if ((ent.z & (kOverflowFlag | kDenseFlag)) == kOverflowFlag) {
+            // a row that found no room in the slot area: its lookups are reduced here, a quarter per wavefront in
+            // ascending order (slow - one gradient fragment in flight - but only batches far from the skew the area
+            // is sized for come here)
+            const uint32_t s0 = a.seg_start[u], len = a.seg_start[u + 1] - s0;
+            const uint32_t q = (len + kSegThreads / kWave - 1) / (kSegThreads / kWave);
+            const uint32_t lo = s0 + ((uint32_t)wv * q < len ? (uint32_t)wv * q : len);
+            const uint32_t hi = s0 + ((uint32_t)(wv + 1) * q < len ? (uint32_t)(wv + 1) * q : len);
+            const GradAddr ga = grad_addr(a, t, D);
+            const GT* gcol = static_cast<const GT*>(a.grad_out) + ga.base;
+            for (uint32_t i = lo; i < hi; ++i) {
+                const uint32_t bag = a.bag_sorted[i];
+                const float sc = bag_scale<MEAN>(a.offsets, bag);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int col = g.lc + c * 256;
+                    if (col < D) {
+                        const float4 f = GradIO<GT>::to_float(GradIO<GT>::load(gcol + ((int64_t)bag - ga.row0) * ga.pitch + col));
+                        acc[c][0] = fmaf(sc, f.x, acc[c][0]); acc[c][1] = fmaf(sc, f.y, acc[c][1]);
+                        acc[c][2] = fmaf(sc, f.z, acc[c][2]); acc[c][3] = fmaf(sc, f.w, acc[c][3]);
+                    }
+                }
+            }
+        }
         for (uint32_t k = (uint32_t)wv; k < nch; k += kSegThreads / kWave) {
             const float* src = a.partial + (size_t)(slot + k) * a.maxD;
 #pragma unroll
@@ -1128,6 +1197,17 @@ __global__ void seq_gbase_kernel(const IdxView offsets, const int32_t* __restric
 }
 
 template <typename GT>
+static void launch_long_update(const SegArgs& a, bool f32, bool mean, hipStream_t s) {
+    if (f32) {
+        if (mean) seg_long_update_kernel<float, true, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<float, false, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+    } else {
+        if (mean) seg_long_update_kernel<__half, true, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<__half, false, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+    }
+}
+
+template <typename GT>
 static void launch_dense_partial(const SegArgs& a, unsigned grid, bool mean, hipStream_t s) {
     if (mean) seg_dense_partial_kernel<true, GT><<<grid, kSegThreads, 0, s>>>(a);
     else seg_dense_partial_kernel<false, GT><<<grid, kSegThreads, 0, s>>>(a);
@@ -1144,7 +1224,6 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.seg_start = reinterpret_cast<const uint32_t*>(ws + w.seg_start);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counters);
     a.counters = counters;
-    a.counters_rw = counters;
     seg_reset_kernel<<<1, 1024, 0, s>>>(counters, reinterpret_cast<uint32_t*>(ws + w.long_tables),
                                         (int)((w.tickets - w.long_tables) / 4) + kTicketWords);
     if (seq)
@@ -1191,7 +1270,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     uint32_t* tbase = tcount + (h->T + 1);
     uint32_t* tfill = tbase + (h->T + 1);
     a.tcount = tcount;
-    a.raw_long = reinterpret_cast<uint2*>(ws + w.raw_long);
+    a.tile_long = reinterpret_cast<uint32_t*>(ws + w.tile_long);
+    a.tile_slots = reinterpret_cast<uint32_t*>(ws + w.tile_slots);
+    a.dense_slot0 = (uint32_t)w.cap_main;
     {   // rows with at most kSegChunk lookups; the others are noted for the long-row path
         LaunchTimer tm(h, s, "seg_update");
         if (grad_io == 0) launch_row_updates<float>(h, a, counters, mean, narrow, wide, s);
@@ -1201,8 +1282,10 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     }
     {
         LaunchTimer tm(h, s, "seg_long_list");
-        seg_long_scan_kernel<<<1, 256, 0, s>>>(tcount, tbase, tfill, h->T, counters);
-        seg_long_fill_kernel<<<512, 256, 0, s>>>(a, counters, tbase, tfill);
+        const unsigned lgrid = (unsigned)(w.long_tiles < 4096 ? w.long_tiles : 4096);
+        seg_long_count_kernel<<<lgrid, 256, 0, s>>>(a);
+        seg_long_scan_kernel<<<1, 1024, 0, s>>>(a, tbase, tfill, counters);
+        seg_long_fill_kernel<<<lgrid, 256, 0, s>>>(a, tbase, tfill);
         if (h->d_hot_ids && !seq) hot_select_kernel<<<h->T, 256, 0, s>>>(a, tbase, h->d_hot_ids, h->d_hot_n);
         if (dense) seg_dense_select_kernel<<<h->T, 256, 0, s>>>(a, tbase);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
@@ -1233,8 +1316,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     {
         LaunchTimer tm(h, s, "seg_long_update");
         // one row per workgroup and round, a dependent chain of loads each: enough workgroups to fill every CU's slots
-        if (f32) seg_long_update_kernel<float><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
-        else seg_long_update_kernel<__half><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        if (grad_io == 0) launch_long_update<float>(a, f32, mean, s);
+        else if (grad_io == 1) launch_long_update<__half>(a, f32, mean, s);
+        else launch_long_update<bf16_t>(a, f32, mean, s);
         tm.done();
     }
     return hipGetLastError();

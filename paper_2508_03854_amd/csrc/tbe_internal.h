@@ -43,7 +43,7 @@ constexpr int kHotRows = 256;           // rows per table that the forward may h
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own
 constexpr int kTicketWords = (kMaxSlices / 8) * 8 * kTicketStride;  // one counter per (sweep, XCD)
-constexpr int kCounterWords = 64;      // device counters: [0]=U [1]=long rows [2]=partial slots [3]=units [4]=long rows noted
+constexpr int kCounterWords = 64;      // device counters: [0]=U [1]=long rows [3]=units
 
 struct TimingSlot {
     const char* name;
@@ -105,14 +105,15 @@ struct Workspace {
     // (pooled calls) or its position (non-pooled calls), so vals[sorted] is the per-lookup stream the gradient
     // kernels read.  After the sort vals[spare] receives unique_rows.
     size_t keys[2], vals[2], bag_of_pos, seg_start, radix_hist, bin_tot, rle_counts, counters, long_tables, tickets, seq_gbase, seg_bounds,
-        seg_chunk0, chunk_desc, dense_rows, dense_n, dense_bounds, raw_long,
+        seg_chunk0, chunk_desc, dense_rows, dense_n, dense_bounds, tile_long, tile_slots,
         long_list, unit_list, bounds, partial, total;
     int radix_blocks;     // blocks a single segment of N keys would need
     int radix_maxc;       // chunk descriptors: radix_blocks + number of segments (every segment may end in a partial chunk)
     int nseg;             // sort segments
     int64_t radix_chunk;  // elements per radix block (multiple of kRadixTile)
     int rle_blocks;
-    int64_t cap_long, cap_chunks, cap_units;
+    int64_t cap_long, cap_main, cap_chunks, cap_units;   // long rows; slots before the dense region; all slots; units
+    int long_tiles;       // tiles of unique rows that the long-row passes walk
     int64_t n;            // number of lookups the workspace was carved for
 };
 Workspace carve(const tbe_handle* h, int64_t N);
