@@ -11,7 +11,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import torch  # must be imported before the library so that both share one HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.environ.get("TBE355_LIB", os.path.join(_HERE, "libtbe355.so"))  # override: A/B tests of builds
+_LIB_PATH = os.path.join(_HERE, "libtbe355.so")
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, EINDEX, EHIP = range(7)
 STATIC_SCRATCH_BYTES = 64 << 20        # TBE_STATIC_SCRATCH_BYTES

@@ -26,8 +26,8 @@ def _newer(target: str, deps) -> bool:
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
-def source_digest(defines=()) -> str:
-    """Twelve hex digits that name the sources (and -D settings) a library is built from; the library reports them
+def source_digest() -> str:
+    """Twelve hex digits that name the sources a library is built from; the library reports them
     through tbe_build_info(), and a counter profile records them, so that measured traffic is only ever attached to
     the kernels it was measured on."""
     import hashlib
@@ -37,18 +37,14 @@ def source_digest(defines=()) -> str:
     for f in files:
         hsh.update(os.path.basename(f).encode())
         hsh.update(open(f, "rb").read())
-    for d in sorted(defines):
-        hsh.update(d.encode())
     return hsh.hexdigest()[:12]
 
 
-def build(force: bool = True, verbose: bool = False, defines=(), lib: str = LIB, obj_dir: str = OBJ) -> str:
-    """defines / lib / obj_dir let an experiment build a variant (-DNAME=VALUE) into another file."""
-    OBJ, LIB = obj_dir, lib  # noqa: N806 - shadow the defaults
+def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(ROOT, "include", "tbe355.h"))
-    digest = source_digest(defines)
+    digest = source_digest()
 
     def compile_one(src: str) -> str:
         s = os.path.join(CSRC, src)
@@ -57,7 +53,7 @@ def build(force: bool = True, verbose: bool = False, defines=(), lib: str = LIB,
         if src == "tbe_api.hip":   # carries the digest of all sources
             deps = deps + [os.path.join(CSRC, f) for f in SOURCES]
         if force or not _newer(o, deps):
-            cmd = [HIPCC] + FLAGS + ["-D" + d for d in defines] + ["-c", s, "-o", o]
+            cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
             if src == "tbe_api.hip":
                 cmd.insert(-4, '-DTBE_SOURCE_DIGEST="%s"' % digest)
             if verbose:

@@ -26,7 +26,7 @@ Workspace carve(const tbe_handle* h, int64_t N) {
     w.keys[1] = take(4 * (n + 1));
     w.vals[0] = take(4 * (n + 1));
     w.vals[1] = take(4 * (n + 1));
-    w.bag_of_pos = take(4 * n);
+    w.bag_of_pos = w.vals[0];   // read by the first radix pass only, which writes keys[1] / vals[1]: no buffer of its own
     w.seg_start = take(4 * (n + 1));
     // radix: G blocks, each owning a contiguous slice that is a whole number of tiles
     int64_t tiles = ((int64_t)n + kRadixTile - 1) / kRadixTile;

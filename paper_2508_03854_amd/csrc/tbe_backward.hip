@@ -28,12 +28,6 @@ __device__ __host__ constexpr int seg_unroll() {
     return NC > 1 ? 4 : (sizeof(GT) == 4 ? (WAVES < 8 ? (MEAN ? 6 : 8) : (MEAN ? 4 : 6)) : 8);
 }
 
-#ifndef TBE_LONG_BLOCKS
-#define TBE_LONG_BLOCKS 2048
-#endif
-#ifndef TBE_SLICE_KB
-#define TBE_SLICE_KB 512
-#endif
 
 struct RowGeom {
     int D, LPR, G, sub, lc;
@@ -246,14 +240,11 @@ __device__ __forceinline__ void adagrad_row(const float (&acc)[NC][4], const Row
 // Hot rows of tables whose gradient block fits the L2 anyway are cut into up to 16 equal parts instead.
 constexpr int kMaxParts = 16;
 constexpr int kMaxPartsSeq = 1024;
-constexpr uint32_t kSliceBytes = (uint32_t)TBE_SLICE_KB << 10;
+constexpr uint32_t kSliceBytes = (uint32_t)512 << 10;
 
 constexpr uint32_t kSlicedFlag = 0x80000000u;
 constexpr uint32_t kDenseFlag = 0x40000000u;   // the row is reduced by the dense-row kernel: no units, kDenseChunks partial sums
-#ifndef TBE_DENSE_DIV
-#define TBE_DENSE_DIV 8
-#endif
-constexpr uint32_t kDenseDiv = TBE_DENSE_DIV;   // a dense row has at least B / kDenseDiv lookups (and at least kDenseMin)
+constexpr uint32_t kDenseDiv = 8;   // a dense row has at least B / kDenseDiv lookups (and at least kDenseMin)
 constexpr uint32_t kDenseMin = 4096;
 constexpr int kDenseMaxCand = 1024;            // candidates per table the selection can rank
 
@@ -280,14 +271,8 @@ __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__
 // kHeavyMin lookups are additionally cut into C units per (XCD, sweep) so that all units are of similar size -
 // otherwise the few heaviest rows would keep their workgroups busy long after the others have moved on to later
 // tables, and the XCD's working set would no longer be one sub-slice.  Other long rows: C equal shares.
-#ifndef TBE_HEAVY_MIN
-#define TBE_HEAVY_MIN 8192
-#endif
-#ifndef TBE_UNIT_LOOKUPS
-#define TBE_UNIT_LOOKUPS 256
-#endif
-constexpr uint32_t kHeavyMin = TBE_HEAVY_MIN;
-constexpr uint32_t kUnitLookups = TBE_UNIT_LOOKUPS;
+constexpr uint32_t kHeavyMin = 8192;
+constexpr uint32_t kUnitLookups = 256;
 struct LongPlan {
     bool sliced;
     uint32_t nsub;    // sub-slices per XCD (sweeps that touch the row)
@@ -591,9 +576,6 @@ __device__ __forceinline__ void long_unit(const SegArgs& a, const uint32_t sweep
     }
 }
 
-#ifndef TBE_TICKET_UNITS
-#define TBE_TICKET_UNITS 1
-#endif
 // Units are handed out in list order, kTicketUnits per wavefront and ticket, through one counter per (sweep, XCD):
 // the units in flight on an XCD are then neighbours in the list (the hot rows of one or two tables), whatever the
 // individual units cost, and the sub-slices they gather from stay in that XCD's L2.  (Walking the list with a
@@ -601,7 +583,7 @@ __device__ __forceinline__ void long_unit(const SegArgs& a, const uint32_t sweep
 template <int NC, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, NC == 1 ? 8 : 4) void seg_long_partial_kernel(const SegArgs a, const uint32_t sweep) {
     constexpr uint32_t kWpb = kSegThreads / kWave;
-    constexpr uint32_t kTicketUnits = TBE_TICKET_UNITS;
+    constexpr uint32_t kTicketUnits = 1;
     __shared__ uint32_t s_ticket;
     const uint32_t nunits = a.counters[3];
     const uint32_t xcd = blockIdx.x & 7u;
@@ -712,10 +694,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_dense_bounds_kernel(const Seg
     }
 }
 
-#ifndef TBE_DENSE_U
-#define TBE_DENSE_U 3
-#endif
-constexpr int kDenseU = TBE_DENSE_U;   // gradient rows in flight per lane group
+constexpr int kDenseU = 3;   // gradient rows in flight per lane group
 template <bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_dense_partial_kernel(const SegArgs a) {
     __shared__ uint32_t s_cnt[kSegThreads / kWave][kWave][kDenseRows];   // per wavefront: counts of a block of 64 bags
@@ -1029,9 +1008,6 @@ __global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const S
 // ---- 4. one workgroup per long row: add its partial sums, then the step ----------------------------------
 // Wavefront w adds slots w, w+4, ... in ascending order, the four sums are added in wavefront order, and
 // wavefront 0 applies the step: a fixed order, so the result does not depend on scheduling.
-#ifndef TBE_LONG_UPDATE_BLOCKS
-#define TBE_LONG_UPDATE_BLOCKS 2048
-#endif
 template <typename WT, bool MEAN, typename GT>
 __global__ __launch_bounds__(kSegThreads) void seg_long_update_kernel(const SegArgs a) {
     __shared__ float s_sum[kSegThreads / kWave][1024];
@@ -1164,8 +1140,8 @@ static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* 
 template <typename GT>
 static void launch_long_partial(const SegArgs& a, uint32_t sweep, bool mean, bool narrow, hipStream_t s) {
     if (narrow) {
-        if (mean) seg_long_partial_kernel<1, true, GT><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sweep);
-        else seg_long_partial_kernel<1, false, GT><<<TBE_LONG_BLOCKS, kSegThreads, 0, s>>>(a, sweep);
+        if (mean) seg_long_partial_kernel<1, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
+        else seg_long_partial_kernel<1, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
     } else {
         if (mean) seg_long_partial_kernel<4, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
         else seg_long_partial_kernel<4, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, sweep);
@@ -1199,11 +1175,11 @@ __global__ void seq_gbase_kernel(const IdxView offsets, const int32_t* __restric
 template <typename GT>
 static void launch_long_update(const SegArgs& a, bool f32, bool mean, hipStream_t s) {
     if (f32) {
-        if (mean) seg_long_update_kernel<float, true, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
-        else seg_long_update_kernel<float, false, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        if (mean) seg_long_update_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
     } else {
-        if (mean) seg_long_update_kernel<__half, true, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
-        else seg_long_update_kernel<__half, false, GT><<<TBE_LONG_UPDATE_BLOCKS, kSegThreads, 0, s>>>(a);
+        if (mean) seg_long_update_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
+        else seg_long_update_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
     }
 }
 
@@ -1289,7 +1265,7 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
         if (h->d_hot_ids && !seq) hot_select_kernel<<<h->T, 256, 0, s>>>(a, tbase, h->d_hot_ids, h->d_hot_n);
         if (dense) seg_dense_select_kernel<<<h->T, 256, 0, s>>>(a, tbase);
         seg_long_units_kernel<<<1, 1024, 0, s>>>(a, counters);
-        if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<2048, kSegThreads, 0, s>>>(a);   // (a chain of ~17 dependent loads per row: many waves)
+        if (slices_for((uint32_t)B, (uint32_t)h->maxD) >= 8u) seg_long_bounds_kernel<<<kSegBlocks, kSegThreads, 0, s>>>(a);   // (a chain of ~17 dependent loads per row: many waves)
         if (dense) seg_dense_bounds_kernel<<<h->T, kSegThreads, 0, s>>>(a);
         tm.done();
     }

@@ -12,15 +12,6 @@
 namespace tbe {
 
 constexpr int kFwdThreads = 256;
-#ifndef TBE_FWD_U
-#define TBE_FWD_U 4
-#endif
-#ifndef TBE_FWD_GROUP_U
-#define TBE_FWD_GROUP_U 8
-#endif
-#ifndef TBE_FWD_WAVES
-#define TBE_FWD_WAVES 8
-#endif
 
 // Lane-group classes: a bag with more ids than this is walked by a whole wavefront instead of one lane group.  The
 // more bags share a wavefront, the more lanes one long bag keeps waiting, so the bound falls with the lanes per row
@@ -110,7 +101,7 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
 // 8 wavefronts per SIMD; the host launches one per width class that has tables.  `tables_of_class` lists the
 // tables this launch covers (those whose rows need more than 64 * (NC / 2) and at most 64 * NC lanes).
 template <typename WT, int NC, int U, bool MEAN>
-__global__ __launch_bounds__(kFwdThreads, NC == 1 ? TBE_FWD_WAVES : 4) void forward_kernel(
+__global__ __launch_bounds__(kFwdThreads, NC == 1 ? 8 : 4) void forward_kernel(
     const WT* __restrict__ weights, const IdxView indices, const IdxView offsets,
     const int32_t* __restrict__ D_off, const int64_t* __restrict__ w_off, const int64_t* __restrict__ row_base,
     const int32_t* __restrict__ tables_of_class, const int32_t n_tables, const int32_t B, const int64_t nnz,
@@ -420,7 +411,7 @@ __global__ __launch_bounds__(kFwdThreads, 4) void forward_long_bags_kernel(
                                         (uint64_t)bcast_lane((uint32_t)((uint64_t)start & 0xFFFFFFFFull), src));
             const int64_t e = (int64_t)(((uint64_t)bcast_lane((uint32_t)((uint64_t)end >> 32), src) << 32) |
                                         (uint64_t)bcast_lane((uint32_t)((uint64_t)end & 0xFFFFFFFFull), src));
-            forward_bag<WT, 1, TBE_FWD_U, MEAN>(weights + w_off[t], D, row_base[t + 1] - row_base[t], indices, s, e, out,
+            forward_bag<WT, 1, 4, MEAN>(weights + w_off[t], D, row_base[t + 1] - row_base[t], indices, s, e, out,
                                                 out_io, (b0 + src) * (int64_t)sumD + d0, err);
         }
     }
@@ -465,20 +456,20 @@ static void launch_forward_groups(const tbe_handle* h, const void* tables, const
         if (h->d_hot_ids && h->hot_min_workgroups >= 0 && (int64_t)n * cpt >= h->hot_min_workgroups) {
             const dim3 hgrid((unsigned)((int64_t)n * cpt));
             if (mean)
-                forward_hot_kernel<WT, TBE_FWD_GROUP_U, true><<<hgrid, kHotThreads, 0, s>>>(
+                forward_hot_kernel<WT, 8, true><<<hgrid, kHotThreads, 0, s>>>(
                     w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io,
                     h->d_err, h->d_hot_ids, h->d_hot_n, cpt);
             else
-                forward_hot_kernel<WT, TBE_FWD_GROUP_U, false><<<hgrid, kHotThreads, 0, s>>>(
+                forward_hot_kernel<WT, 8, false><<<hgrid, kHotThreads, 0, s>>>(
                     w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io,
                     h->d_err, h->d_hot_ids, h->d_hot_n, cpt);
             continue;
         }
         if (mean)
-            forward_groups_kernel<WT, TBE_FWD_GROUP_U, true><<<grid, kFwdThreads, 0, s>>>(
+            forward_groups_kernel<WT, 8, true><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
         else
-            forward_groups_kernel<WT, TBE_FWD_GROUP_U, false><<<grid, kFwdThreads, 0, s>>>(
+            forward_groups_kernel<WT, 8, false><<<grid, kFwdThreads, 0, s>>>(
                 w, indices, offsets, d_D_off, h->d_w_off, h->d_row_base, list, n, lpr_log2, B, nnz, h->sumD, out, out_io, h->d_err);
     }
     // the bags those launches left out (the four classes' tables follow one another in the list)
@@ -505,12 +496,12 @@ hipError_t launch_forward(const tbe_handle* h, const void* tables, const int32_t
     LaunchTimer tm(h, s, "forward_pool");
     const bool mean = pooling == TBE_MEAN;
     if (h->dtype == TBE_F32) {
-        launch_forward_nc<float, 1, TBE_FWD_U>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<float, 1, 4>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_nc<float, 2, 4>(h, 5, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_nc<float, 4, 2>(h, 6, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_groups<float>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     } else {
-        launch_forward_nc<__half, 1, TBE_FWD_U>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
+        launch_forward_nc<__half, 1, 4>(h, 0, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_nc<__half, 2, 4>(h, 5, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
         launch_forward_groups<__half>(h, tables, d_D_off, indices, offsets, B, nnz, mean, out, out_io, s);
     }

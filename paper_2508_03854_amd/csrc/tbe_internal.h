@@ -11,34 +11,16 @@
 namespace tbe {
 
 // ---- tunables that fix the workspace layout -------------------------------------------------
-#ifndef TBE_SEG_CHUNK
-#define TBE_SEG_CHUNK 512
-#endif
-constexpr int kSegChunk = TBE_SEG_CHUNK;         // a unique row with more lookups than this is split into chunks of this size
-#ifndef TBE_RADIX_TILE
-#define TBE_RADIX_TILE 4096
-#endif
-constexpr int kRadixTile = TBE_RADIX_TILE;  // elements per radix-sort tile (256 threads x items per thread)
-#ifndef TBE_RADIX_MAX_BLOCKS
-#define TBE_RADIX_MAX_BLOCKS 8192
-#endif
-constexpr int kRadixMaxBlocks = TBE_RADIX_MAX_BLOCKS;  // each radix block owns one contiguous slice of the input
-#ifndef TBE_RLE_TILE
-#define TBE_RLE_TILE 2048
-#endif
-constexpr int kRleTile = TBE_RLE_TILE;  // elements per run-length tile (at most 4096: one wavefront scans its runs of 64)
+constexpr int kSegChunk = 512;         // a unique row with more lookups than this is split into chunks of this size
+constexpr int kRadixTile = 4096;  // elements per radix-sort tile (256 threads x items per thread)
+constexpr int kRadixMaxBlocks = 8192;  // each radix block owns one contiguous slice of the input
+constexpr int kRleTile = 2048;  // elements per run-length tile (at most 4096: one wavefront scans its runs of 64)
 constexpr int kLinTile = 2048;         // positions per linearize tile
 constexpr int kMaxSlices = 64;         // sub-slices of one table's gradient block (8 XCDs x up to 8 sweeps)
 constexpr int kMaxSortSegments = 4096;  // tables beyond this are sorted as one segment on the linearised key
-#ifndef TBE_DENSE_ROWS
-#define TBE_DENSE_ROWS 16
-#endif
-constexpr int kDenseRows = TBE_DENSE_ROWS;   // rows per table that the dense-row kernel reduces (multiple of 4)
+constexpr int kDenseRows = 16;   // rows per table that the dense-row kernel reduces (multiple of 4)
 constexpr int kDenseChunks = 32;            // bag chunks (= partial sums) per dense row
-#ifndef TBE_FWD_GROUP_MAX_LANES
-#define TBE_FWD_GROUP_MAX_LANES 32
-#endif
-constexpr int kFwdGroupMaxLanes = TBE_FWD_GROUP_MAX_LANES;   // rows of at most this many lanes use one bag per lane group
+constexpr int kFwdGroupMaxLanes = 32;   // rows of at most this many lanes use one bag per lane group
 constexpr int kHotRows = 256;           // rows per table that the forward may hold in LDS (the handle's hot-row list)
 constexpr int kMaxReplicas = 16;        // replicas of one buffer that tbe_replica_mean averages in one call
 constexpr int kTicketStride = 32;       // words between two ticket counters: each sits in a 128-byte line of its own

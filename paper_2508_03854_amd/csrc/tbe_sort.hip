@@ -231,10 +231,7 @@ __device__ __forceinline__ void hist_add(uint32_t* __restrict__ hw, const uint32
 // Private histograms per wavefront: lanes are spread over kHistCopies of them, which divides the number of lanes
 // that meet on one LDS word or bank (the kernel is bound by these LDS additions, not by the key stream: 1.04 ms with
 // one copy, 0.83 ms with two, for the three passes of the largest workload).
-#ifndef TBE_HIST_COPIES
-#define TBE_HIST_COPIES 2
-#endif
-constexpr int kHistCopies = TBE_HIST_COPIES;
+constexpr int kHistCopies = 2;
 __global__ __launch_bounds__(kRsThreads) void radix_hist_kernel(const uint32_t* __restrict__ keys, const SortPlan pl,
                                                                 const int shift, const uint32_t mask, const int nbins,
                                                                 uint32_t* __restrict__ ghist) {
