@@ -216,7 +216,7 @@ constexpr int kHotThreads = 1024;
 constexpr int kHotWaves = kHotThreads / kWave;
 constexpr int kHotTab = 1024;                // slots of the id table (at most kHotRows ids: a quarter full)
 constexpr int kHotRowBytes = 64 << 10;       // LDS bytes for rows
-constexpr int kHotPasses = 16;               // rounds of kHotWaves * G bags per workgroup
+constexpr int kHotPasses = 8;               // rounds of kHotWaves * G bags per workgroup
 constexpr uint32_t kHotEmpty = 0xFFFFFFFFu;
 
 __device__ __forceinline__ uint32_t hot_hash(const uint32_t id) { return (id * 0x9E3779B1u) >> 22; }   // 10 bits
