@@ -16,7 +16,9 @@ p_counter_collection.csv, written by (run from the repo root, after `cd /tmp && 
     rocprofv3 --pmc WRITE_SIZE --kernel-include-regex "tbe::" -d <dir>/write -o p --output-format csv -- python3 bench.py <ARGS>
     rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum --kernel-include-regex "tbe::" -d <dir>/cache -o p --output-format csv -- python3 bench.py <ARGS>
 
-with <ARGS> = --workload <WL> --steps 5 --warmup 2 --pool 2 --no-cpu-baseline.
+with <ARGS> = --workload <WL> --steps 5 --warmup 2 --pool 2 --no-cpu-baseline.  If <dir> also holds latency/ and issue/
+(two more counter runs of the same command, listed in LATENCY_PASSES), <WL>_latency_counters.md is written too: read
+latency past the vector L1, read requests in flight per compute unit, instruction counts per wavefront.
 """
 from __future__ import annotations
 
@@ -28,6 +30,13 @@ import json
 import os
 
 ARGS = "--workload {wl} --steps 5 --warmup 2 --pool 2 --no-cpu-baseline"
+
+LATENCY_PASSES = {
+    "latency": "TCP_TCC_READ_REQ_LATENCY_sum TCP_TCC_READ_REQ_sum TCP_PENDING_STALL_CYCLES_sum TCP_TOTAL_CACHE_ACCESSES_sum",
+    "issue": "SQ_WAVES SQ_BUSY_CYCLES SQ_WAIT_INST_ANY SQ_INSTS_VMEM_RD SQ_INSTS_VALU SQ_INSTS_SALU GRBM_GUI_ACTIVE",
+}
+COMPUTE_UNITS = 256
+XCDS = 8   # GRBM_GUI_ACTIVE comes back summed over the chip's 8 dies (8 x 2.3e9 per second of kernel time)
 
 # kernel (name without template arguments) -> timing record of tbe_timing_read / bench.py
 RECORD = {
@@ -158,6 +167,39 @@ def main() -> None:
                    "write_scale": w_scale, "bytes_per_step": {k: round(v) for k, v in sorted(per_record.items())}}, f, indent=1)
         f.write("\n")
     print(open(os.path.join(a.out, f"{wl}_hbm_traffic.md")).read())
+
+    # ---- latency and issue counters (optional passes)
+    if not all(os.path.isdir(os.path.join(src, sub)) for sub in LATENCY_PASSES):
+        return
+    lat, iss = load_counters(src, "latency"), load_counters(src, "issue")
+    avg_us = {short(r["Name"]): float(r["AverageNs"]) / 1e3 for r in tbe}
+    with open(os.path.join(a.out, f"{wl}_latency_counters.md"), "w") as f:
+        f.write(f"# rocprofv3 --pmc latency and issue counters, workload {wl}\n\nLibrary: `{bench['build']}`\n\n")
+        f.write("Commands (one counter set per run):\n\n")
+        for c in LATENCY_PASSES.values():
+            f.write(f"    rocprofv3 --pmc {c} --kernel-include-regex \"tbe::\" -d out -o p --output-format csv -- python3 bench.py {args}\n")
+        f.write("\nPer launch (mean over the launches seen). `latency` = TCP_TCC_READ_REQ_LATENCY / TCP_TCC_READ_REQ: clock "
+                "cycles per read request that left a vector L1. `cycles` = GRBM_GUI_ACTIVE / 8 (the counter is summed over the "
+                f"8 dies). `requests / cycle / CU` = read requests / (cycles x {COMPUTE_UNITS}); x 128 bytes x 256 CUs x the "
+                "clock it is the request bandwidth the kernel drew past the L1s. `in flight per CU` = that rate x latency "
+                "(Little's law): the mean number of read requests one compute unit had outstanding. The calibration gathers "
+                "(random slices of known size; <16>: window in L2, <32, false>: in the Infinity Cache, <64> and <8>: HBM, "
+                "<32, true>: HBM, read-modify-write) show what the memory system gives each level: deeper queues buy "
+                "latency, not rate. `avg us` is the kernel-trace duration of the stats run.\n\n")
+        f.write("| kernel | avg us | wavefronts | VALU insts / wave | SALU insts / wave | VMEM reads / wave | L1->L2 read requests | "
+                "latency (cycles) | requests / cycle / CU | in flight per CU | L1 pending-stall cycles / cycle |\n"
+                "|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|\n")
+        for k in sorted(lat, key=lambda k: -avg_us.get(k, 0.0)):
+            if k not in iss:
+                continue
+            rq = mean(lat[k]["TCP_TCC_READ_REQ_sum"])
+            lc = mean(lat[k]["TCP_TCC_READ_REQ_LATENCY_sum"]) / max(1.0, rq)
+            waves = max(1.0, mean(iss[k]["SQ_WAVES"]))
+            active = max(1.0, mean(iss[k]["GRBM_GUI_ACTIVE"]) / XCDS)
+            stall = mean(lat[k]["TCP_PENDING_STALL_CYCLES_sum"]) / (active * COMPUTE_UNITS)
+            f.write(f"| `{k}` | {avg_us.get(k, 0.0):.1f} | {waves:.3g} | {mean(iss[k]['SQ_INSTS_VALU']) / waves:.0f} | "
+                    f"{mean(iss[k]['SQ_INSTS_SALU']) / waves:.0f} | {mean(iss[k]['SQ_INSTS_VMEM_RD']) / waves:.1f} | {rq:.3g} | "
+                    f"{lc:.0f} | {rq / (active * COMPUTE_UNITS):.4f} | {rq * lc / (active * COMPUTE_UNITS):.1f} | {stall:.2f} |\n")
 
 
 if __name__ == "__main__":
