@@ -144,7 +144,10 @@ static double bag_scale(const int64_t* offsets, int64_t bag, int pooling) {
 }
 
 /* ---- forward -------------------------------------------------------------------------------- */
-/* One bag:  out_row[j] = s * sum_{p in bag} W_t[indices[p], j].  Returns -1 on an id outside [0, R_t). */
+/* One bag:  out_row[j] = sum_{p in bag} W_t[indices[p], j], for mean pooling divided by the number of ids L
+ * (a division, as the mean is defined: a product with the rounded reciprocal 1/L would be one more rounding, and
+ * would break the tie of a 16-bit output whose exact mean lies half-way between two values by its own error).
+ * Returns -1 on an id outside [0, R_t). */
 int oracle_forward_bag_io(const void* table, int dtype, int64_t R, int32_t D, const int64_t* indices,
                           int64_t start, int64_t end, int pooling, void* out, int out_io, int64_t out_elem) {
     double* acc = (double*)calloc((size_t)D, sizeof(double));
@@ -154,8 +157,11 @@ int oracle_forward_bag_io(const void* table, int dtype, int64_t R, int32_t D, co
         for (int32_t j = 0; j < D; ++j) acc[j] += load_w(table, dtype, r * D + j);
     }
     int64_t L = end - start;
-    double s = (pooling == ORACLE_SUM) ? 1.0 : (L > 0 ? 1.0 / (double)L : 0.0);
-    for (int32_t j = 0; j < D; ++j) store_io(out, out_io, out_elem + j, s * acc[j]);
+    for (int32_t j = 0; j < D; ++j) {
+        double x = acc[j];
+        if (pooling != ORACLE_SUM) x = L > 0 ? x / (double)L : 0.0;
+        store_io(out, out_io, out_elem + j, x);
+    }
     free(acc);
     return 0;
 }

@@ -390,6 +390,26 @@ def test_16bit_output_is_the_fp64_sum_rounded_once(oracle_mod):
     assert np.array_equal((back.astype(np.float32).view(np.uint32) & 0xFFFF), np.zeros(exact.shape, dtype=np.uint32))
 
 
+def test_mean_of_equal_rows_is_the_row_also_where_a_16bit_output_ties(oracle_mod):
+    # mean(w, w, ..., w) = w.  Every binary16 pattern of a small exponent range as table values: one in eight of them
+    # lies exactly half-way between two bfloat16 values, so the bfloat16 output must be the row rounded to nearest
+    # even - which a mean formed as sum * (1/L) misses for some L by the rounding error of the reciprocal.
+    bits = np.arange(0x2000, 0x2400, dtype=np.uint16)                 # 1024 consecutive positive binary16 values
+    Wt = np.concatenate([bits, bits | 0x8000]).view(np.float16).reshape(1, -1)
+    as_f32 = Wt.astype(np.float32).view(np.uint32).astype(np.uint64)
+    rne_bf16 = ((as_f32 + 0x7FFF + ((as_f32 >> 16) & 1)) >> 16).astype(np.uint16)   # float32 -> bfloat16, ties to even
+    assert ((as_f32 & 0xFFFF) == 0x8000).sum() == Wt.size // 8         # the ties are really there
+    for L in (1, 3, 7, 10, 49, 127, 200):
+        idx = np.zeros(L, dtype=np.int64)
+        off = np.array([0, L], dtype=np.int64)
+        assert np.array_equal(oracle_mod.forward([Wt], idx, off, 1, "mean").view(np.uint32),
+                              Wt.astype(np.float32).view(np.uint32)), L
+        assert np.array_equal(oracle_mod.forward([Wt], idx, off, 1, "mean", out_dtype="f16").view(np.uint16),
+                              Wt.view(np.uint16)), L
+        assert np.array_equal(oracle_mod.forward([Wt], idx, off, 1, "mean", out_dtype="bf16").view(np.uint16),
+                              rne_bf16), L
+
+
 @pytest.mark.parametrize("io", ["f16", "bf16"])
 def test_16bit_gradient_equals_its_exact_float32_image(oracle_mod, io):
     # a 16-bit upstream gradient converts to float32 without error, so the step must equal the float32 step
