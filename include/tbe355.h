@@ -124,7 +124,8 @@ tbe_status tbe_backward_rowwise_adagrad_ex(const tbe_handle* h, const void* grad
  * TBE_STATIC_SCRATCH_BYTES - is refused with TBE_EWORKSPACE before anything is launched.  All calls on one GPU share
  * that GPU's array, whatever the handle: two such calls that overlap in time on one GPU (different streams or
  * threads) race, so serialise them; the array keeps the last call's contents, and the kernels clear what they need
- * cleared themselves.  tbe_debug_sorted does not apply to it. */
+ * cleared themselves.  tbe_debug_sorted does not apply to it, and its kernels are not recorded by tbe_timing_* (the
+ * first recording of a kernel creates its events). */
 #define TBE_STATIC_SCRATCH_BYTES (64u << 20)
 tbe_status tbe_backward_rowwise_adagrad_static(const tbe_handle* h, const void* grad_out, tbe_io_dtype grad_dtype,
                                                const void* indices, const void* offsets, tbe_index_dtype index_dtype,

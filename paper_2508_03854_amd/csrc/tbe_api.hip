@@ -370,8 +370,15 @@ tbe_status tbe_backward_rowwise_adagrad_static(const tbe_handle* h, const void* 
     if (st != TBE_OK) return st;
     if (carve(h, nnz).total > (size_t)TBE_STATIC_SCRATCH_BYTES) return TBE_EWORKSPACE;   // beyond the fixed array
     if (!h->static_scratch) return TBE_EHIP;
-    return backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps, momentum_scale,
-                         tables, state, h->static_scratch, (size_t)TBE_STATIC_SCRATCH_BYTES, hip_stream);
+    // per-kernel timing creates events and grows a host-side list on first use: not in a call that allocates nothing
+    tbe_handle* hm = const_cast<tbe_handle*>(h);
+    const bool timing = hm->timing;
+    hm->timing = false;
+    const tbe_status r = backward_impl(h, grad_out, grad_dtype, indices, offsets, index_dtype, B, nnz, pooling, lr, eps,
+                                       momentum_scale, tables, state, h->static_scratch, (size_t)TBE_STATIC_SCRATCH_BYTES,
+                                       hip_stream);
+    hm->timing = timing;
+    return r;
 }
 
 tbe_status tbe_backward_prepare(const tbe_handle* h, const void* indices, const void* offsets,

@@ -22,6 +22,17 @@ __device__ __host__ __forceinline__ int long_bag_min(const int lanes_per_row) {
 }
 
 // NC = number of 64-lane column chunks a row needs (1 when D <= 64 * kVec); U = rows in flight per group.
+// The pooled value that is stored: the sum, or for mean pooling sum / L - the product with the reciprocal, corrected
+// once by its exact residual (the usual refinement step of a division), so that a mean that is exactly representable
+// (a bag whose ids are all equal, say) comes out exact and a 16-bit `out` rounds it the way the definition does.
+// An empty bag has L = 0 and inv = 0: the result is the (zero) sum.
+template <bool MEAN>
+__device__ __forceinline__ float pooled(const float sum, const float L, const float inv) {
+    if (!MEAN) return sum;
+    const float q = sum * inv;
+    return fmaf(fmaf(-q, L, sum), inv, q);
+}
+
 template <typename WT, int NC, int U, bool MEAN>
 __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const int D, const int64_t R,
                                             const IdxView indices, const int64_t start, const int64_t end,
@@ -77,10 +88,11 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
 #pragma unroll
             for (int v = 0; v < V; ++v) acc[c][v] += __shfl_xor(acc[c][v], o, kWave);
     }
-    float scale = 1.f;
+    float scale = 1.f, lenf = 0.f;
     if (MEAN) {
         const int64_t L = end - start;
-        scale = L > 0 ? 1.f / (float)L : 0.f;
+        lenf = (float)L;
+        scale = L > 0 ? 1.f / lenf : 0.f;
     }
     if (sub == 0) {
 #pragma unroll
@@ -89,8 +101,9 @@ __device__ __forceinline__ void forward_bag(const WT* __restrict__ table, const 
             if (col < D) {
 #pragma unroll
                 for (int v4 = 0; v4 < V; v4 += 4) {
-                    store4_from_float(out, out_io, out_elem + col + v4, acc[c][v4] * scale, acc[c][v4 + 1] * scale,
-                                      acc[c][v4 + 2] * scale, acc[c][v4 + 3] * scale);
+                    store4_from_float(out, out_io, out_elem + col + v4, pooled<MEAN>(acc[c][v4], lenf, scale),
+                                      pooled<MEAN>(acc[c][v4 + 1], lenf, scale), pooled<MEAN>(acc[c][v4 + 2], lenf, scale),
+                                      pooled<MEAN>(acc[c][v4 + 3], lenf, scale));
                 }
             }
         }
@@ -191,14 +204,16 @@ __global__ __launch_bounds__(kFwdThreads, 8) void forward_groups_kernel(
             for (int u = 0; u < U; ++u) RowIO<WT>::accumulate(x[u], acc);
         }
     }
+    const float lenf = (float)len;
     float scale = 1.f;
-    if (MEAN) scale = len > 0 ? 1.f / (float)len : 0.f;
+    if (MEAN) scale = len > 0 ? 1.f / lenf : 0.f;
     if (has_bag && col_on && !is_long) {
         const int64_t out_elem = b * (int64_t)sumD + d0 + lc;
 #pragma unroll
         for (int v4 = 0; v4 < V; v4 += 4)
-            store4_from_float(out, out_io, out_elem + v4, acc[v4] * scale, acc[v4 + 1] * scale, acc[v4 + 2] * scale,
-                              acc[v4 + 3] * scale);
+            store4_from_float(out, out_io, out_elem + v4, pooled<MEAN>(acc[v4], lenf, scale),
+                              pooled<MEAN>(acc[v4 + 1], lenf, scale), pooled<MEAN>(acc[v4 + 2], lenf, scale),
+                              pooled<MEAN>(acc[v4 + 3], lenf, scale));
     }
 }
 
@@ -356,14 +371,16 @@ __global__ __launch_bounds__(kHotThreads, 8) void forward_hot_kernel(
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the lists are free for the next round
         }
+        const float lenf = (float)len;
         float scale = 1.f;
-        if (MEAN) scale = len > 0 ? 1.f / (float)len : 0.f;
+        if (MEAN) scale = len > 0 ? 1.f / lenf : 0.f;
         if (has_bag && col_on && !is_long) {
             const int64_t out_elem = b * (int64_t)sumD + d0 + lc;
 #pragma unroll
             for (int v4 = 0; v4 < V; v4 += 4)
-                store4_from_float(out, out_io, out_elem + v4, acc[v4] * scale, acc[v4 + 1] * scale, acc[v4 + 2] * scale,
-                                  acc[v4 + 3] * scale);
+                store4_from_float(out, out_io, out_elem + v4, pooled<MEAN>(acc[v4], lenf, scale),
+                                  pooled<MEAN>(acc[v4 + 1], lenf, scale), pooled<MEAN>(acc[v4 + 2], lenf, scale),
+                                  pooled<MEAN>(acc[v4 + 3], lenf, scale));
         }
     }
 }

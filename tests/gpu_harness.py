@@ -34,7 +34,22 @@ def split_flat(flat_np: np.ndarray, cfg: W.Config):
     return [flat_np[woff[t]:woff[t + 1]].reshape(cfg.rows[t], cfg.D[t]) for t in range(cfg.T)]
 
 
-def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, scale: float, what: str):
+def forward_scale(cfg: W.Config, off_np: np.ndarray, B: int):
+    """Operand magnitude per element of the pooled output, the `scale` of assert_close: max|w|, and for a sum over more
+    than 64 ids max|w| * L/64 - the rounding error of an fp32 sum is bounded relative to the sum of the operands'
+    magnitudes (about L * max|w| / 2 here), not to a result that may have cancelled.  The fixed scale covers bags of up
+    to ~80 ids (rtol * max|w| = 4 * 2^-24 * 84 * max|w|/2); the factor keeps the same bound per operand beyond that.
+    Mean pooling divides sum and error by L, so its scale stays max|w|."""
+    f = np.ones((B, cfg.sum_D))
+    if cfg.pooling == "sum":
+        lens = np.diff(np.asarray(off_np, dtype=np.int64)).reshape(cfg.T, B)
+        d_off = cfg.D_offsets()
+        for t in range(cfg.T):
+            f[:, d_off[t]:d_off[t + 1]] = np.maximum(1.0, lens[t] / 64.0)[:, None]
+    return cfg.w_scale * f
+
+
+def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, scale, what: str):
     got64, ref64 = got.astype(np.float64), ref.astype(np.float64)
     err = np.abs(got64 - ref64)
     tol = rtol * np.abs(ref64) + rtol * scale
@@ -105,14 +120,14 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
     assert not tbe.poll_index_error()
     fwd_rtol = RTOL_F32 if (cfg.weight_dtype == "f32" or same_inputs) else RTOL_F16
     if io == "f32":
-        report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, w_scale, "forward")
+        report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, forward_scale(cfg, off_np, B), "forward")
     else:
         # 16-bit output: the fp32 sum is rounded once.  Values: the fp32 tolerance plus one unit in the last place
         # of the format.  Where the sum did not cancel (|ref| >= scale/10, so the fp32 error is far below the
         # format's spacing) the result is the oracle's value or, rarely, its neighbour.
         ulp_rel = 2.0 ** -10 if io == "f16" else 2.0 ** -7
         ref64 = decode16(out_ref, io)
-        report["fwd_max_err"] = assert_close(decode16(out_gpu, io), ref64, fwd_rtol + ulp_rel, w_scale, "forward")
+        report["fwd_max_err"] = assert_close(decode16(out_gpu, io), ref64, fwd_rtol + ulp_rel, forward_scale(cfg, off_np, B), "forward")
         if same_inputs:
             big = np.abs(ref64) >= 0.1 * w_scale
             d = ulp16_distance(out_gpu, out_ref)[big]
