@@ -34,18 +34,21 @@ def split_flat(flat_np: np.ndarray, cfg: W.Config):
     return [flat_np[woff[t]:woff[t + 1]].reshape(cfg.rows[t], cfg.D[t]) for t in range(cfg.T)]
 
 
-def forward_scale(cfg: W.Config, off_np: np.ndarray, B: int):
-    """Operand magnitude per element of the pooled output, the `scale` of assert_close: max|w|, and for a sum over more
-    than 64 ids max|w| * L/64 - the rounding error of an fp32 sum is bounded relative to the sum of the operands'
-    magnitudes (about L * max|w| / 2 here), not to a result that may have cancelled.  The fixed scale covers bags of up
-    to ~80 ids (rtol * max|w| = 4 * 2^-24 * 84 * max|w|/2); the factor keeps the same bound per operand beyond that.
-    Mean pooling divides sum and error by L, so its scale stays max|w|."""
-    f = np.ones((B, cfg.sum_D))
+def forward_scale(cfg: W.Config, off_np: np.ndarray, B: int, same_inputs: bool):
+    """Operand magnitude per element of the pooled output, the `scale` of assert_close.
+    While both sides pool bit-identical weights: max|w|, and for a sum-pooled bag of L > 42 ids max|w| * L/42, i.e. an
+    absolute term of 4 * 2^-24 * L * max|w| - four units in the last place of the largest partial sum the bag can
+    reach (every fp32 addition rounds at the magnitude of the running sum, which the final value, after cancellation,
+    may be far below; observed: 1.5e-7 on a 509-id bag whose sum is 0.0027).
+    After a step each side pools its OWN weights, which agree only to the weight tolerance (up to 2 * rtol * max|w|
+    per element); over a sum-pooled bag of L ids - L copies of one row's difference, if the bag repeats a row - these
+    add up, so 2 L is added.  Mean pooling divides sum and error by L: its scale is max|w|, resp. 3 max|w|."""
+    f = np.full((B, cfg.sum_D), 1.0 if same_inputs else 3.0)
     if cfg.pooling == "sum":
-        lens = np.diff(np.asarray(off_np, dtype=np.int64)).reshape(cfg.T, B)
+        lens = np.diff(np.asarray(off_np, dtype=np.int64)).reshape(cfg.T, B).astype(np.float64)
         d_off = cfg.D_offsets()
         for t in range(cfg.T):
-            f[:, d_off[t]:d_off[t + 1]] = np.maximum(1.0, lens[t] / 64.0)[:, None]
+            f[:, d_off[t]:d_off[t + 1]] = (np.maximum(1.0, lens[t] / 42.0) + (0.0 if same_inputs else 2.0 * lens[t]))[:, None]
     return cfg.w_scale * f
 
 
@@ -120,20 +123,24 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
     assert not tbe.poll_index_error()
     fwd_rtol = RTOL_F32 if (cfg.weight_dtype == "f32" or same_inputs) else RTOL_F16
     if io == "f32":
-        report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, forward_scale(cfg, off_np, B), "forward")
+        report["fwd_max_err"] = assert_close(out_gpu, out_ref, fwd_rtol, forward_scale(cfg, off_np, B, same_inputs), "forward")
     else:
         # 16-bit output: the fp32 sum is rounded once.  Values: the fp32 tolerance plus one unit in the last place
         # of the format.  Where the sum did not cancel (|ref| >= scale/10, so the fp32 error is far below the
         # format's spacing) the result is the oracle's value or, rarely, its neighbour.
         ulp_rel = 2.0 ** -10 if io == "f16" else 2.0 ** -7
         ref64 = decode16(out_ref, io)
-        report["fwd_max_err"] = assert_close(decode16(out_gpu, io), ref64, fwd_rtol + ulp_rel, forward_scale(cfg, off_np, B), "forward")
+        report["fwd_max_err"] = assert_close(decode16(out_gpu, io), ref64, fwd_rtol + ulp_rel, forward_scale(cfg, off_np, B, same_inputs), "forward")
         if same_inputs:
             big = np.abs(ref64) >= 0.1 * w_scale
             d = ulp16_distance(out_gpu, out_ref)[big]
             if d.size:
                 assert d.max() <= 1, f"{io} forward: {int(d.max())} ulps from the oracle"
-                assert (d > 0).sum() <= max(2, 2e-3 * d.size), f"{int((d > 0).sum())}/{d.size} {io} outputs round differently"
+                # how often the fp32 and the fp64 sum straddle a rounding boundary of the format grows with the
+                # fp32 sum's error, i.e. with the number of terms: 2e-3 up to 32 ids per bag, in proportion beyond
+                longest = int(np.diff(np.asarray(off_np, dtype=np.int64)).max()) if len(off_np) > 1 else 0
+                rate16 = 2e-3 * max(1.0, longest / 32.0)
+                assert (d > 0).sum() <= max(2, rate16 * d.size), f"{int((d > 0).sum())}/{d.size} {io} outputs round differently"
                 report["fwd_ulp_mismatch_frac"] = float((d > 0).mean())
 
     # ---- backward + optimizer
@@ -162,6 +169,8 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
     gpu_tabs = split_flat(flat_np, cfg)
     touched = np.zeros(cfg.total_rows, dtype=bool)
     touched[res.unique_rows] = True
+    hits = np.zeros(cfg.total_rows, dtype=np.int64)      # lookups per row
+    hits[res.unique_rows] = np.diff(res.seg_start)
     base = cfg.row_base()
     # untouched rows keep their bits (weights and moments)
     iv = np.uint32 if cfg.weight_dtype == "f32" else np.uint16
@@ -179,11 +188,14 @@ def check_step(cfg: W.Config, tbe: TBE, flat: torch.Tensor, state: torch.Tensor,
             werr = max(werr, assert_close(gpu_tabs[t][m], tabs[t][m], RTOL_F32, w_scale, f"weights of table {t}"))
             if same_inputs:
                 # the step itself (Algorithm 1, step 6): w_after - w_before on both sides, to 1e-5 of the row's
-                # largest update plus the rounding of the subtraction (one fp32 ulp of the weights)
+                # largest update plus the rounding of the subtraction (one fp32 ulp of the weights).  A row whose
+                # gradient is an fp32 sum of n terms of either sign carries that sum's error, about sqrt(n) * 2^-24
+                # of the result; four times that replaces 1e-5 where it is larger (rows with more than ~1750 lookups).
                 dw_g = gpu_tabs[t][m].astype(np.float64) - prev_tabs[t][m].astype(np.float64)
                 dw_r = tabs[t][m].astype(np.float64) - prev_tabs[t][m].astype(np.float64)
                 row_max = np.abs(dw_r).max(axis=1, keepdims=True)
-                bound = RTOL_F32 * row_max + 2.0 ** -23 * (np.abs(prev_tabs[t][m]).astype(np.float64) + np.abs(dw_r))
+                row_rtol = np.maximum(RTOL_F32, 4.0 * np.sqrt(hits[base[t]:base[t + 1]][m]) * 2.0 ** -24)[:, None]
+                bound = row_rtol * row_max + 2.0 ** -23 * (np.abs(prev_tabs[t][m]).astype(np.float64) + np.abs(dw_r))
                 bad = np.abs(dw_g - dw_r) > bound
                 assert not bad.any(), (f"updates of table {t}: {int(bad.sum())} elements outside 1e-5 of the row's step; "
                                        f"worst {np.abs(dw_g - dw_r).max():.3e}")
