@@ -189,10 +189,11 @@ tbe_status tbe_backward_seq_rowwise_adagrad(const tbe_handle* h, const void* gra
  * replicas that live on this one device:  x^(j) <- (1/M) * sum_m x^(m)  for every replica j, element by element.
  * Call it once on the replicas' `tables` buffers (dtype of the handle) and once on their `state` buffers
  * (TBE_F32).  Across devices this step is an all-reduce and is not part of this library.
- *   replicas  HOST array of M DEVICE pointers (1 <= M <= 16), pairwise distinct, each 16-byte aligned, `count`
- *             elements of `dtype`; read and overwritten in place
+ *   replicas  HOST array of M DEVICE pointers (1 <= M <= 16), each 16-byte aligned, `count` elements of `dtype`,
+ *             no two of the M buffers sharing a byte; read and overwritten in place
  * The sum runs over the replicas in index order in fp32 and is divided by M; binary16 buffers are rounded once,
- * to nearest even.  M == 1 leaves the buffer untouched.  TBE_EINVAL for a null, misaligned or repeated pointer. */
+ * to nearest even.  M == 1 leaves the buffer untouched.  TBE_EINVAL for a null or misaligned pointer, a repeated one, or buffers
+ * that overlap. */
 tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, size_t count, tbe_dtype dtype,
                             void* hip_stream);
 

@@ -228,7 +228,6 @@ tbe_status tbe_create(int32_t T, const int64_t* rows, const int32_t* D, tbe_dtyp
     h->d_row_base = reinterpret_cast<int64_t*>(base + b_doff);
     h->d_w_off = reinterpret_cast<int64_t*>(base + b_doff + b_rb);
     h->d_err = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo);
-    h->d_zero = base + b_doff + b_rb + b_wo + 128;
     h->d_fwd_tables = reinterpret_cast<int32_t*>(base + b_doff + b_rb + b_wo + 256);
     if (keep_hot) {   // (zeroed below: no hot rows until a backward call has listed some)
         h->d_hot_ids = reinterpret_cast<uint32_t*>(base + b_doff + b_rb + b_wo + 256 + b_cls);
@@ -477,10 +476,14 @@ tbe_status tbe_replica_mean(tbe_handle* h, void* const* replicas, int32_t M, siz
                             void* hip_stream) {
     if (!h || !replicas || M < 1 || M > kMaxReplicas) return TBE_EINVAL;
     if (dtype != TBE_F32 && dtype != TBE_F16) return TBE_EDTYPE;
+    const size_t bytes = count * (dtype == TBE_F32 ? 4u : 2u);
     for (int m = 0; m < M; ++m) {
         if (!replicas[m] || !aligned(replicas[m], 16)) return TBE_EINVAL;
-        for (int k = 0; k < m; ++k)
-            if (replicas[k] == replicas[m]) return TBE_EINVAL;   // two replicas in one buffer would race
+        const uintptr_t a0 = reinterpret_cast<uintptr_t>(replicas[m]);
+        for (int k = 0; k < m; ++k) {   // two replicas that share bytes would race (equal pointers, or ranges that overlap)
+            const uintptr_t b0 = reinterpret_cast<uintptr_t>(replicas[k]);
+            if (a0 == b0 || (a0 < b0 + bytes && b0 < a0 + bytes)) return TBE_EINVAL;
+        }
     }
     if (count == 0 || M == 1) return TBE_OK;   // the mean over one replica is that replica
     const hipError_t e = launch_replica_mean(h, replicas, M, count, dtype == TBE_F32, static_cast<hipStream_t>(hip_stream));

@@ -63,7 +63,6 @@ struct SegArgs {
     const uint32_t* counters;     // [0]=U, [1]=long rows, [3]=work units
     const uint32_t* bag_sorted;   // the sorted payload: linear bag id of every sorted lookup
     IdxView offsets;
-    const void* zeros;            // 128 bytes of zeros, never written
     const void* grad_out;         // [B, sum(D)] float / binary16 / bfloat16, per the kernel's GT (or the sequence layout)
     const int64_t* seq_gbase;     // non-pooled mode only: element offset of table t's gradient block minus start_t * D_t
     int seq;                      // 1: non-pooled; bag_sorted then holds the original positions
@@ -318,13 +317,13 @@ struct LongRow {
     int t;
     LongPlan p;
 };
-__device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U) {
+// (len = the row's number of lookups, 0 for u >= U: loaded by the caller, for all of a thread's rows before any is looked at)
+__device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U, const uint32_t len) {
     LongRow r;
     r.is_long = false;
     r.t = 0;
     r.p.sliced = false; r.p.nsub = 1; r.p.C = 0; r.p.nslots = 0;
     if (u >= U) return r;
-    const uint32_t len = a.seg_start[u + 1] - a.seg_start[u];
     if (len <= (uint32_t)kSegChunk) return r;
     const uint32_t key = a.keys_unique[u];
     if (key >= a.total_rows) return r;   // the pseudo-row of invalid ids
@@ -342,9 +341,16 @@ __global__ __launch_bounds__(256) void seg_long_count_kernel(const SegArgs a) {
         if (threadIdx.x == 0) s_n = s_slots = 0u;
         __syncthreads();
         uint32_t n = 0, slots = 0;
+        uint32_t len[kLongTile / 256];
+#pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const LongRow r = long_row(a, u, U);
+            len[k] = u < U ? a.seg_start[u + 1] - a.seg_start[u] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kLongTile / 256; ++k) {
+            const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
+            const LongRow r = long_row(a, u, U, len[k]);
             if (r.is_long) {
                 ++n;
                 slots += r.p.nslots;
@@ -409,9 +415,16 @@ __global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, con
     for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         if (a.tile_long[tile + 1 < ntiles ? tile + 1 : tile] == a.tile_long[tile] && tile + 1 < ntiles) continue;   // no long row here
         uint32_t slot_run = a.tile_slots[tile];       // slots of the long rows before this tile
+        uint32_t len[kLongTile / 256];
+#pragma unroll
+        for (int k = 0; k < kLongTile / 256; ++k) {
+            const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
+            len[k] = u < U ? a.seg_start[u + 1] - a.seg_start[u] : 0u;
+        }
+#pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {   // (rows k*256 .. k*256+255 of the tile, in row order)
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const LongRow r = long_row(a, u, U);
+            const LongRow r = long_row(a, u, U, len[k]);
             uint32_t tot;
             const uint32_t slot = slot_run + block_excl_scan<256>(r.is_long ? r.p.nslots : 0u, smem, &tot);
             slot_run += tot;
@@ -803,7 +816,7 @@ __global__ __launch_bounds__(kSegThreads, kDenseRows <= 16 ? 3 : 2) void seg_den
 // kSegWaves = wavefronts per SIMD the kernel is compiled and launched for: 8, or 7 with more fragments in flight; the
 // host picks (see the launch).
 template <typename WT, bool MEAN, typename GT, int kSegWaves>
-__global__ __launch_bounds__(kSegThreads, kSegWaves) void seg_update_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+__global__ __launch_bounds__(kSegThreads, kSegWaves) void seg_update_kernel(const SegArgs a) {
     constexpr int kSegUnroll = seg_unroll<1, MEAN, GT, kSegWaves>();
     const int lane = lane_id();
     const uint32_t U = a.counters[0];
@@ -978,7 +991,7 @@ __global__ __launch_bounds__(kSegThreads, kSegWaves) void seg_update_kernel(cons
 
 // ---- 3b. same rows, any width up to 1024 columns: one wavefront per row ----------------------------
 template <typename WT, bool MEAN, typename GT>
-__global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const SegArgs a, uint32_t* __restrict__ counters) {
+__global__ __launch_bounds__(kSegThreads, 4) void seg_update_wide_kernel(const SegArgs a) {
     const uint32_t U = a.counters[0];
     const uint32_t nwaves = gridDim.x * (kSegThreads / kWave);
     WT* tables = static_cast<WT*>(a.tables);
@@ -1104,8 +1117,8 @@ __global__ __launch_bounds__(1024) void seg_reset_kernel(uint32_t* __restrict__ 
 
 // the two row-update kernels and the hot-row reduction for one gradient element type
 template <typename GT>
-static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* counters, bool mean, bool narrow,
-                               bool wide, hipStream_t s) {
+static void launch_row_updates(const tbe_handle* h, const SegArgs& a, bool mean, bool narrow, bool wide,
+                               hipStream_t s) {
     const bool f32 = h->dtype == TBE_F32;
     if (narrow) {
         // every CU filled once; 7 wavefronts per SIMD for 32-bit gradients on binary16 tables when most of their rows
@@ -1113,26 +1126,26 @@ static void launch_row_updates(const tbe_handle* h, const SegArgs& a, uint32_t* 
         // same widths, which therefore keep 8)
         if (sizeof(GT) == 4 && !f32 && h->seg_mostly_wavefront_rows) {
             const unsigned grid = 256u * 7u;
-            if (mean) seg_update_kernel<__half, true, GT, 7><<<grid, kSegThreads, 0, s>>>(a, counters);
-            else seg_update_kernel<__half, false, GT, 7><<<grid, kSegThreads, 0, s>>>(a, counters);
+            if (mean) seg_update_kernel<__half, true, GT, 7><<<grid, kSegThreads, 0, s>>>(a);
+            else seg_update_kernel<__half, false, GT, 7><<<grid, kSegThreads, 0, s>>>(a);
         } else {
             const unsigned grid = 256u * 8u;
             if (f32) {
-                if (mean) seg_update_kernel<float, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_kernel<float, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+                if (mean) seg_update_kernel<float, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a);
+                else seg_update_kernel<float, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a);
             } else {
-                if (mean) seg_update_kernel<__half, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
-                else seg_update_kernel<__half, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a, counters);
+                if (mean) seg_update_kernel<__half, true, GT, 8><<<grid, kSegThreads, 0, s>>>(a);
+                else seg_update_kernel<__half, false, GT, 8><<<grid, kSegThreads, 0, s>>>(a);
             }
         }
     }
     if (wide) {
         if (f32) {
-            if (mean) seg_update_wide_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            else seg_update_wide_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            if (mean) seg_update_wide_kernel<float, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
+            else seg_update_wide_kernel<float, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
         } else {
-            if (mean) seg_update_wide_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
-            else seg_update_wide_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a, counters);
+            if (mean) seg_update_wide_kernel<__half, true, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
+            else seg_update_wide_kernel<__half, false, GT><<<kSegBlocks, kSegThreads, 0, s>>>(a);
         }
     }
 }
@@ -1208,7 +1221,6 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.bag_sorted = reinterpret_cast<const uint32_t*>(ws + w.vals[spare ^ 1]);   // the sorted payload stream
     a.offsets = IdxView{offsets, idx32};
     a.grad_out = grad_out;
-    a.zeros = h->d_zero;
     a.D_off = h->d_D_off;
     a.row_base = h->d_row_base;
     a.w_off = h->d_w_off;
@@ -1251,9 +1263,9 @@ hipError_t launch_segment_update(const tbe_handle* h, const Workspace& w, char* 
     a.dense_slot0 = (uint32_t)w.cap_main;
     {   // rows with at most kSegChunk lookups; the others are noted for the long-row path
         LaunchTimer tm(h, s, "seg_update");
-        if (grad_io == 0) launch_row_updates<float>(h, a, counters, mean, narrow, wide, s);
-        else if (grad_io == 1) launch_row_updates<__half>(h, a, counters, mean, narrow, wide, s);
-        else launch_row_updates<bf16_t>(h, a, counters, mean, narrow, wide, s);
+        if (grad_io == 0) launch_row_updates<float>(h, a, mean, narrow, wide, s);
+        else if (grad_io == 1) launch_row_updates<__half>(h, a, mean, narrow, wide, s);
+        else launch_row_updates<bf16_t>(h, a, mean, narrow, wide, s);
         tm.done();
     }
     {

@@ -217,12 +217,6 @@ struct RowIO<float> {
     }
     // 4-element fragment used by the optimizer step (one lane owns 4 columns)
     static __device__ __forceinline__ void load4(const float* p, float (&x)[4]) { load(p, x); }
-    // the same fragment as it travels: loaded early, converted when the step is applied
-    using raw4_t = float4;
-    static __device__ __forceinline__ raw4_t load_raw4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-    static __device__ __forceinline__ void raw4_to_float(const raw4_t& r, float (&x)[4]) {
-        x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
-    }
     static __device__ __forceinline__ void store4(float* p, const float (&x)[4]) {
         *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
     }
@@ -256,14 +250,6 @@ struct RowIO<__half> {
     }
     static __device__ __forceinline__ void load4(const __half* p, float (&x)[4]) {
         const uint2 raw = *reinterpret_cast<const uint2*>(p);
-        x[0] = __half2float(__ushort_as_half((unsigned short)(raw.x & 0xFFFFu)));
-        x[1] = __half2float(__ushort_as_half((unsigned short)(raw.x >> 16)));
-        x[2] = __half2float(__ushort_as_half((unsigned short)(raw.y & 0xFFFFu)));
-        x[3] = __half2float(__ushort_as_half((unsigned short)(raw.y >> 16)));
-    }
-    using raw4_t = uint2;
-    static __device__ __forceinline__ raw4_t load_raw4(const __half* p) { return *reinterpret_cast<const uint2*>(p); }
-    static __device__ __forceinline__ void raw4_to_float(const raw4_t& raw, float (&x)[4]) {
         x[0] = __half2float(__ushort_as_half((unsigned short)(raw.x & 0xFFFFu)));
         x[1] = __half2float(__ushort_as_half((unsigned short)(raw.x >> 16)));
         x[2] = __half2float(__ushort_as_half((unsigned short)(raw.y & 0xFFFFu)));

@@ -60,7 +60,6 @@ struct tbe_handle {
     int64_t* d_w_off = nullptr;     // [T+1]
     void* static_scratch = nullptr; // device address, on this handle's device, of the library's fixed scratch array
     int32_t* d_err = nullptr;       // sticky invalid-id flag
-    const void* d_zero = nullptr;   // 128 bytes of zeros (never written): what a lane with nothing to fetch reads
     // Forward classes: 0, 5, 6 = one wavefront per bag, rows of at most 64 / 128 / 256 sixteen-byte fragments;
     // 1..4 = narrow rows (32 / 16 / 8 / <=4 lanes per row), where every lane group of a wavefront takes a bag of its
     // own (2 / 4 / 8 / 16 bags per wavefront).  d_fwd_tables lists the tables class by class.

@@ -97,5 +97,9 @@ def test_replica_mean_values_tail_and_argument_checks(H):
     mis = (ctypes.c_void_p * 2)(a.data_ptr(), a.data_ptr() + 4)
     assert L.tbe_replica_mean(tbe._h, mis, 2, 8, P.F32, torch.cuda.current_stream().cuda_stream) == P.EINVAL
     assert L.tbe_replica_mean(tbe._h, two, 17, 64, P.F32, torch.cuda.current_stream().cuda_stream) == P.EINVAL
+    # distinct, aligned pointers whose ranges overlap: 32 floats starting 16 floats apart
+    lap = (ctypes.c_void_p * 2)(a.data_ptr(), a.data_ptr() + 64)
+    assert L.tbe_replica_mean(tbe._h, lap, 2, 32, P.F32, torch.cuda.current_stream().cuda_stream) == P.EINVAL
+    assert L.tbe_replica_mean(tbe._h, lap, 2, 16, P.F32, torch.cuda.current_stream().cuda_stream) == P.OK   # adjacent
     assert L.tbe_replica_mean(tbe._h, two, 2, 64, 7, torch.cuda.current_stream().cuda_stream) == P.EDTYPE
     tbe.close()
