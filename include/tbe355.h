@@ -19,8 +19,9 @@
  *   - Pooled output / upstream gradient: float32 [B, sum(D)] row-major; bag (t, b) maps to columns
  *     D_offsets[t] .. D_offsets[t+1]-1 of row b.
  *   - Every pointer argument marked DEVICE is device memory owned by the caller; HOST pointers are read
- *     during the call only.  The library allocates device memory only in tbe_create (a few KB of table
- *     metadata) and never in the two hot calls.
+ *     during the call only.  The library allocates device memory only in tbe_create (table metadata: a few KB,
+ *     plus 1 KB per table for the forward's hot-row hint) and never in the hot calls; its device image also
+ *     holds the TBE_STATIC_SCRATCH_BYTES array of tbe_backward_rowwise_adagrad_static.
  *   - The hot calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and return without synchronising.  They are safe to capture into a HIP graph.
  *   - Limits: 4 <= D[t] <= 1024 and D[t] % 4 == 0 (% 8 for fp16 weights); rows[t] < 2^31;
