@@ -345,7 +345,9 @@ __global__ __launch_bounds__(256) void seg_long_count_kernel(const SegArgs a) {
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            len[k] = u < U ? a.seg_start[u + 1] - a.seg_start[u] : 0u;
+            const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
+            const uint32_t l = a.seg_start[uc + 1] - a.seg_start[uc];
+            len[k] = u < U ? l : 0u;
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
@@ -419,7 +421,9 @@ __global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, con
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            len[k] = u < U ? a.seg_start[u + 1] - a.seg_start[u] : 0u;
+            const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
+            const uint32_t l = a.seg_start[uc + 1] - a.seg_start[uc];
+            len[k] = u < U ? l : 0u;
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {   // (rows k*256 .. k*256+255 of the tile, in row order)

@@ -519,10 +519,24 @@ constexpr int kRleItems = kRleTile / kRleThreads;            // 8
 constexpr int kRleRuns = kRleItems * (kRleThreads / kWave);  // runs of 64 elements per tile
 static_assert(kRleRuns <= kWave, "one wavefront scans the run counts of a tile");
 
-__device__ __forceinline__ bool is_head(const uint32_t* __restrict__ keys, int64_t i, int64_t N) {
-    if (i >= N) return false;
-    if (i == 0) return true;
-    return keys[i] != keys[i - 1];
+// Head flags of a thread's kRleItems elements (element k*kRleThreads + tid of the tile): element i is a head if it
+// exists and its key differs from its predecessor's.  The loads are unconditional (indices clamped into the array,
+// which always holds at least one element) and all issued before the first comparison, so that they overlap.
+__device__ __forceinline__ void head_flags(const uint32_t* __restrict__ keys, const int64_t base, const int64_t N,
+                                           bool (&head)[kRleItems]) {
+    uint32_t cur[kRleItems], prev[kRleItems];
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) {
+        const int64_t i = base + k * kRleThreads + threadIdx.x;
+        const bool in = i < N;
+        cur[k] = keys[in ? i : 0];
+        prev[k] = keys[(in && i > 0) ? i - 1 : 0];
+    }
+#pragma unroll
+    for (int k = 0; k < kRleItems; ++k) {
+        const int64_t i = base + k * kRleThreads + threadIdx.x;
+        head[k] = i < N && (i == 0 || cur[k] != prev[k]);
+    }
 }
 
 __global__ __launch_bounds__(kRleThreads) void rle_count_kernel(const uint32_t* __restrict__ keys, const int64_t N,
@@ -530,9 +544,10 @@ __global__ __launch_bounds__(kRleThreads) void rle_count_kernel(const uint32_t* 
     __shared__ uint32_t s_w[kRleThreads / kWave];
     const int64_t base = (int64_t)blockIdx.x * kRleTile;
     uint32_t c = 0;   // heads seen by this wavefront: one ballot and one population count per run of 64 keys
+    bool head[kRleItems];
+    head_flags(keys, base, N, head);
 #pragma unroll
-    for (int k = 0; k < kRleItems; ++k)
-        c += (uint32_t)__popcll(__ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N)));
+    for (int k = 0; k < kRleItems; ++k) c += (uint32_t)__popcll(__ballot(head[k]));
     if (lane_id() == 0) s_w[threadIdx.x >> 6] = c;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -584,9 +599,11 @@ __global__ __launch_bounds__(kRleThreads) void rle_write_kernel(const uint32_t* 
     if (tile >= (uint32_t)ntiles) return;
     const int64_t base = (int64_t)tile * kRleTile;
     uint64_t heads[kRleItems];
+    bool head[kRleItems];
+    head_flags(keys, base, N, head);
 #pragma unroll
     for (int k = 0; k < kRleItems; ++k) {
-        heads[k] = __ballot(is_head(keys, base + k * kRleThreads + threadIdx.x, N));
+        heads[k] = __ballot(head[k]);
         if (lane == 0) s_run[k * (kRleThreads / kWave) + w] = (uint32_t)__popcll(heads[k]);
     }
     __syncthreads();
