@@ -317,8 +317,10 @@ struct LongRow {
     int t;
     LongPlan p;
 };
-// (len = the row's number of lookups, 0 for u >= U: loaded by the caller, for all of a thread's rows before any is looked at)
-__device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U, const uint32_t len) {
+// (s0 = seg_start[u], len = the row's number of lookups, 0 for u >= U: loaded by the caller, for all of a thread's rows
+// before any is looked at)
+__device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U, const uint32_t s0,
+                                            const uint32_t len) {
     LongRow r;
     r.is_long = false;
     r.t = 0;
@@ -328,7 +330,8 @@ __device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, 
     const uint32_t key = a.keys_unique[u];
     if (key >= a.total_rows) return r;   // the pseudo-row of invalid ids
     r.is_long = true;
-    r.t = table_of_key(a.row_base, a.T, key);
+    // the table: from the bag of the row's first lookup where the payload is a bag (one load instead of a search)
+    r.t = a.seq ? table_of_key(a.row_base, a.T, key) : (int)(a.bag_sorted[s0] / (uint32_t)a.B);
     r.p = long_plan((uint32_t)a.B, (uint32_t)(a.D_off[r.t + 1] - a.D_off[r.t]), len, a.seq != 0);
     return r;
 }
@@ -341,18 +344,18 @@ __global__ __launch_bounds__(256) void seg_long_count_kernel(const SegArgs a) {
         if (threadIdx.x == 0) s_n = s_slots = 0u;
         __syncthreads();
         uint32_t n = 0, slots = 0;
-        uint32_t len[kLongTile / 256];
+        uint32_t start[kLongTile / 256], len[kLongTile / 256];
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
             const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
-            const uint32_t l = a.seg_start[uc + 1] - a.seg_start[uc];
-            len[k] = u < U ? l : 0u;
+            start[k] = a.seg_start[uc];
+            len[k] = u < U ? a.seg_start[uc + 1] - start[k] : 0u;
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const LongRow r = long_row(a, u, U, len[k]);
+            const LongRow r = long_row(a, u, U, start[k], len[k]);
             if (r.is_long) {
                 ++n;
                 slots += r.p.nslots;
@@ -417,18 +420,18 @@ __global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, con
     for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         if (a.tile_long[tile + 1 < ntiles ? tile + 1 : tile] == a.tile_long[tile] && tile + 1 < ntiles) continue;   // no long row here
         uint32_t slot_run = a.tile_slots[tile];       // slots of the long rows before this tile
-        uint32_t len[kLongTile / 256];
+        uint32_t start[kLongTile / 256], len[kLongTile / 256];
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
             const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
-            const uint32_t l = a.seg_start[uc + 1] - a.seg_start[uc];
-            len[k] = u < U ? l : 0u;
+            start[k] = a.seg_start[uc];
+            len[k] = u < U ? a.seg_start[uc + 1] - start[k] : 0u;
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {   // (rows k*256 .. k*256+255 of the tile, in row order)
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const LongRow r = long_row(a, u, U, len[k]);
+            const LongRow r = long_row(a, u, U, start[k], len[k]);
             uint32_t tot;
             const uint32_t slot = slot_run + block_excl_scan<256>(r.is_long ? r.p.nslots : 0u, smem, &tot);
             slot_run += tot;
