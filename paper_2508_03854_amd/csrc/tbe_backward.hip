@@ -317,8 +317,8 @@ struct LongRow {
     int t;
     LongPlan p;
 };
-// (s0 = seg_start[u], len = the row's number of lookups, 0 for u >= U: loaded by the caller, for all of a thread's rows
-// before any is looked at)
+// (s0 = seg_start[u], len = the row's number of lookups, anything for u >= U: loaded by the caller, for all of a
+// thread's rows before any is looked at)
 __device__ __forceinline__ LongRow long_row(const SegArgs& a, const uint32_t u, const uint32_t U, const uint32_t s0,
                                             const uint32_t len) {
     LongRow r;
@@ -348,9 +348,11 @@ __global__ __launch_bounds__(256) void seg_long_count_kernel(const SegArgs a) {
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
+            // unconditional loads, so that they overlap: a row behind the last reads row 0 (seg_start always has two
+            // entries), and long_row looks at no length of a row that does not exist
+            const uint32_t uc = u < U ? u : 0u;
             start[k] = a.seg_start[uc];
-            len[k] = u < U ? a.seg_start[uc + 1] - start[k] : 0u;
+            len[k] = a.seg_start[uc + 1] - start[k];
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
@@ -424,9 +426,11 @@ __global__ __launch_bounds__(256) void seg_long_fill_kernel(const SegArgs a, con
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {
             const uint32_t u = tile * kLongTile + k * 256 + threadIdx.x;
-            const uint32_t uc = u < U ? u : 0u;   // (unconditional loads: they overlap; seg_start always has two entries)
+            // unconditional loads, so that they overlap: a row behind the last reads row 0 (seg_start always has two
+            // entries), and long_row looks at no length of a row that does not exist
+            const uint32_t uc = u < U ? u : 0u;
             start[k] = a.seg_start[uc];
-            len[k] = u < U ? a.seg_start[uc + 1] - start[k] : 0u;
+            len[k] = a.seg_start[uc + 1] - start[k];
         }
 #pragma unroll
         for (int k = 0; k < kLongTile / 256; ++k) {   // (rows k*256 .. k*256+255 of the tile, in row order)
