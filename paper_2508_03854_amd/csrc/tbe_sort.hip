@@ -107,18 +107,47 @@ __global__ __launch_bounds__(kLinThreads) void linearize_kernel(const IdxView in
 #pragma unroll
         for (int k = 0; k < kItems; ++k) own[k] = own[k] > prev ? own[k] : prev;
     }
+    // The ids and the row ranges of all of a thread's positions first (a position behind the tile's end reads the
+    // tile's last one), pinned in registers here: left to itself the compiler moves every load into the branch that
+    // uses it and waits for it there, one position after the other.
+    int64_t idv[kItems], bagv[kItems], rbv[kItems], rev[kItems];
+    if (indices.is32) {
+        const int32_t* q = static_cast<const int32_t*>(indices.p);
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) {
+            const int64_t p = p0 + w * (kWave * kItems) + k * kWave + lane;
+            idv[k] = (int64_t)q[p < p1 ? p : p1 - 1];
+        }
+    } else {
+        const int64_t* q = static_cast<const int64_t*>(indices.p);
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) {
+            const int64_t p = p0 + w * (kWave * kItems) + k * kWave + lane;
+            idv[k] = q[p < p1 ? p : p1 - 1];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int64_t p = p0 + w * (kWave * kItems) + k * kWave + lane;
+        int64_t bag;
+        if (staged) bag = lo + own[k];
+        else bag = upper_bound_i64(offsets, lo, hi + 1, p < p1 ? p : p1 - 1) - 1;   // a tile spanning more than kLinTile bags (runs of empty bags)
+        bag = bag < lo ? lo : (bag > hi ? hi : bag);
+        bagv[k] = bag;
+        const int32_t t = (int32_t)(bag / B);
+        rbv[k] = row_base[t];
+        rev[k] = row_base[t + 1];
+    }
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) asm volatile("" : "+v"(idv[k]), "+v"(rbv[k]), "+v"(rev[k]));
 #pragma unroll
     for (int k = 0; k < kItems; ++k) {
         const int64_t p = p0 + w * (kWave * kItems) + k * kWave + lane;
         if (p >= p1) continue;
-        int64_t bag;
-        if (staged) bag = lo + own[k];
-        else bag = upper_bound_i64(offsets, lo, hi + 1, p) - 1;   // a tile spanning more than kLinTile bags (runs of empty bags)
-        bag = bag < lo ? lo : (bag > hi ? hi : bag);
-        const int32_t t = (int32_t)(bag / B);
-        const int64_t rb = row_base[t];
-        const int64_t R = row_base[t + 1] - rb;
-        const int64_t id = indices[p];
+        const int64_t bag = bagv[k];
+        const int64_t rb = rbv[k];
+        const int64_t R = rev[k] - rb;
+        const int64_t id = idv[k];
         // local_keys: the table-local id (an invalid id gets R, one past the table's last row); the sort's last
         // pass turns it into the linearised key
         uint32_t key;
