@@ -362,12 +362,23 @@ __device__ __forceinline__ uint32_t scatter_tile(
 
     uint32_t key[kRsItems], val[kRsItems], off[kRsItems];
     const int64_t wbase = tile + (int64_t)w * (kWave * kRsItems);
+    if (iota_vals) {   // the payload is the position itself (the branch sits outside the loop: inside it the compiler
+                       // waits for every key before it goes on to the next)
 #pragma unroll
-    for (int k = 0; k < kRsItems; ++k) {
-        const int64_t i = wbase + k * kWave + lane;
-        const bool valid = FULL || i < e;
-        key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
-        val[k] = valid ? (iota_vals ? (uint32_t)i : vals_in[i]) : 0u;  // iota: the payload is the position itself
+        for (int k = 0; k < kRsItems; ++k) {
+            const int64_t i = wbase + k * kWave + lane;
+            const bool valid = FULL || i < e;
+            key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
+            val[k] = valid ? (uint32_t)i : 0u;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRsItems; ++k) {
+            const int64_t i = wbase + k * kWave + lane;
+            const bool valid = FULL || i < e;
+            key[k] = valid ? keys_in[i] : 0xFFFFFFFFu;
+            val[k] = valid ? vals_in[i] : 0u;
+        }
     }
     // Rank inside the wave, item by item in input order.  peers = the valid lanes that hold the same digit: per digit
     // bit one ballot, and the lanes that agree with this lane's bit are  ~(ballot ^ (all ones if the bit is set)).
