@@ -230,7 +230,8 @@ def main():
     # gather calibration: random slices of known size from a window that fits an L2 (2 MiB per XCD), the Infinity
     # Cache (32 MiB shared) or neither (2 GiB per XCD), and the same with every slice written back - what this box
     # delivers for the access pattern of the embedding kernels.  (Slice sizes differ per case only so that the cases
-    # carry different kernel names in a profile; rates do not depend on the size from 128 bytes up.)
+    # carry different kernel names in a profile; rates do not depend on the size from 128 bytes up.  The two small
+    # read-modify-write cases are the pieces a row would be cut into if every XCD owned an eighth of its columns.)
     gather = None
     if args.gather_gib > 0:
         g_buf = torch.zeros(args.gather_gib << 30, dtype=torch.uint8, device=dev)
@@ -238,7 +239,8 @@ def main():
         per_xcd_big = (args.gather_gib << 30) // 8
         cases = [("l2_resident_256B", 2 << 20, 256, True, False), ("infinity_cache_512B", 32 << 20, 512, False, False),
                  ("hbm_1KiB", per_xcd_big, 1024, True, False), ("hbm_128B", per_xcd_big, 128, True, False),
-                 ("hbm_rmw_512B", per_xcd_big, 512, True, True)]
+                 ("hbm_rmw_512B", per_xcd_big, 512, True, True), ("hbm_rmw_64B", per_xcd_big, 64, True, True),
+                 ("hbm_rmw_32B", per_xcd_big, 32, True, True)]
         gather = {}
         for name, window, sl, per_xcd, wb in cases:
             n = int(4e9 // sl)

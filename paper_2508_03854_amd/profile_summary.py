@@ -135,7 +135,8 @@ def main() -> None:
                 continue
             targ = k.split("<")[1].split(">")[0].replace(" ", "").split(",")
             lpr, rmw = int(targ[0]), targ[1] == "true"
-            case = "hbm_rmw_512B" if rmw else ("infinity_cache_512B" if lpr == 32 else lpr_case.get(lpr))
+            rmw_case = {32: "hbm_rmw_512B", 4: "hbm_rmw_64B", 2: "hbm_rmw_32B"}
+            case = rmw_case.get(lpr) if rmw else ("infinity_cache_512B" if lpr == 32 else lpr_case.get(lpr))
             if not case or case not in g:
                 continue
             known = g[case]["slices"] * g[case]["slice_bytes"]
