@@ -142,7 +142,9 @@ def main() -> None:
             known = g[case]["slices"] * g[case]["slice_bytes"]
             seen = mean(fetch[k]["FETCH_SIZE"]) * 1024 * f_scale
             f.write(f"| `{k}` | {case} | {known / 1e9:.2f} GB | {seen / 1e9:.2f} GB | {seen / known:.2f} |\n")
-        f.write("\n(An L2-resident window reads next to nothing past the L2; windows beyond the caches should read ~1.0.)\n\n")
+        f.write("\n(An L2-resident window reads next to nothing past the L2; windows beyond the caches should read ~1.0; slices "
+                "of less than 128 bytes read more than they use - the L2 fetches whole 128-byte lines: 2.0 at 64 bytes, 4.0 "
+                "at 32.)\n\n")
         f.write("Per launch, scaled (GB = 1e9 bytes). FETCH_SIZE counts what the L2 asks of the fabric, whether the "
                 "Infinity Cache or HBM serves it. L2 hit = TCC_HIT / (TCC_HIT + TCC_MISS).\n\n")
         f.write("| kernel | launches seen | read GB | written GB | L2 hit % | L1->L2 read requests |\n|---|---:|---:|---:|---:|---:|\n")
