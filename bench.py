@@ -88,6 +88,76 @@ def algorithmic_bytes(cfg, nnz, U_t, ib=8, eb=4):
     }
 
 
+def side_mode(args, torch, W, TBE, build):
+    """The widened entry points, timed the same way (HIP events per kernel on the launch stream, wall clock over the
+    timed steps): one record, not the headline metric."""
+    dev = "cuda"
+    base = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "data": "synthetic", "build": build}
+    if args.mode == "sync":
+        # weight sync / moment sync of Algorithm 1 for M replicas held on this device, 1 GiB per replica
+        tbe = TBE([16], [8], "f32")
+        out = {}
+        for name, dt, eb in (("f32", torch.float32, 4), ("f16", torch.float16, 2)):
+            for M in (2, 4, 8):
+                reps = [torch.empty((1 << 30) // eb, dtype=dt, device=dev).normal_() for _ in range(M)]
+                tbe.timing_enable(True)
+                for _ in range(args.warmup + args.steps):
+                    tbe.replica_mean(reps)
+                ms = [m for n, m in tbe.timing_read() if n == "replica_mean"][args.warmup:]
+                t = sum(ms) / len(ms)
+                out[f"{name}_M{M}"] = {"ms": t, "read_plus_write_GBps": 2 * M * (1 << 30) / (t * 1e-3) / 1e9}
+                del reps
+        best = max(v["read_plus_write_GBps"] for v in out.values())
+        return dict(base, metric="GB/s read+written, replica mean (Algorithm 1 weight / moment sync) on one device",
+                    value=best, unit="GB/s", ms_per_step=None, dtype="f32",
+                    config={"workload": "M replicas of 1 GiB each, M in {2, 4, 8}"}, cases=out)
+    # ---- the non-pooled lookup and its backward
+    cfg = W.config(args.workload, rows_scale=args.rows_scale)
+    io_t = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.io]
+    flat = torch.empty(cfg.total_elems, dtype=cfg.torch_weight_dtype, device=dev)
+    W.fill_weights(cfg, flat)
+    state = torch.zeros(cfg.total_rows, dtype=torch.float32, device=dev)
+    (idx, off), = W.make_batches(cfg, [0], device=dev)
+    idx, toff, total = W.as_sequence(cfg, idx, off)
+    if args.index_dtype == "i32":
+        idx, toff = idx.to(torch.int32), toff.to(torch.int32)
+    g = W.make_grad_seq(cfg, total, 0, device=dev).to(io_t)
+    out = torch.empty(total, dtype=io_t, device=dev)
+    tbe = TBE(cfg.rows, cfg.D, cfg.weight_dtype)
+    ws = tbe.alloc_workspace(1, idx.numel())
+
+    def step():
+        tbe.lookup_seq(flat, idx, toff, out)
+        tbe.backward_seq_rowwise_adagrad(g, idx, toff, flat, state, ws, lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    acc = {}
+    reps = max(2, min(args.steps, 4))
+    for _ in range(reps):
+        tbe.timing_enable(True)
+        step()
+        for n, ms in tbe.timing_read():
+            acc[n] = acc.get(n, 0.0) + ms / reps
+    assert not tbe.poll_index_error()
+    nnz = int(idx.numel())
+    lookup_bytes = total * (flat.element_size() + out.element_size()) + nnz * idx.element_size()
+    return dict(base, metric="lookups/sec, non-pooled lookup + its backward with row-wise AdaGrad", unit="lookups/s",
+                value=nnz * args.steps / elapsed, ms_per_step=1e3 * elapsed / max(1, args.steps), dtype="f32",
+                config={"workload": W.describe(cfg) + " (ids read as one sequence per table)", "index_dtype": args.index_dtype,
+                        "io_dtype": args.io, "lookups_per_step": nnz, "out_bytes": total * out.element_size()},
+                kernels_ms_per_step=acc,
+                lookup_seq={"ms": acc.get("lookup_seq"), "read_plus_write_GBps": lookup_bytes / (acc["lookup_seq"] * 1e-3) / 1e9},
+                backward_ms=sum(v for n, v in acc.items() if n != "lookup_seq"))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +180,9 @@ def main():
                          "launch-bound workloads)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     ap.add_argument("--gather-gib", type=int, default=16, help="buffer of the gather calibration in GiB (0 = skip)")
+    ap.add_argument("--mode", choices=["step", "seq", "sync"], default="step",
+                    help="step: the pooled forward + backward (the metric); seq: the non-pooled lookup and its backward "
+                         "on the workload's ids read as sequences; sync: the replica mean of Algorithm 1 on one device")
     ap.add_argument("--hot-rows-min-workgroups", type=int, default=None,
                     help="tunable of the forward's on-chip hot-row path (negative: off; default: the library's)")
     args = ap.parse_args()
@@ -126,6 +199,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
+    if args.mode != "step":
+        print(json.dumps(side_mode(args, torch, W, TBE, build_info())))
+        return
     cfg = W.config(args.workload, rows_scale=args.rows_scale,
                    **({} if args.momentum_scale is None else {"c": args.momentum_scale}))
     log("workload:", W.describe(cfg), "" if args.rows_scale == 1.0 else f"[rows scaled by {args.rows_scale}]")
