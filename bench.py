@@ -180,6 +180,9 @@ def main():
                          "launch-bound workloads)")
     ap.add_argument("--copy-mib", type=int, default=2048, help="size of the streaming-copy calibration (0 = skip)")
     ap.add_argument("--gather-gib", type=int, default=16, help="buffer of the gather calibration in GiB (0 = skip)")
+    ap.add_argument("--sort-stream", action="store_true",
+                    help="the backward in two calls, its gradient-free half (sort / dedup) on a second stream next to "
+                         "the forward of the same batch")
     ap.add_argument("--mode", choices=["step", "seq", "sync"], default="step",
                     help="step: the pooled forward + backward (the metric); seq: the non-pooled lookup and its backward "
                          "on the workload's ids read as sequences; sync: the replica mean of Algorithm 1 on one device")
@@ -219,7 +222,7 @@ def main():
     # the committed counter profiles cover the default call variant of the full-size workload only, and only the
     # library build they were measured on
     default_call = not extended and args.rows_scale == 1.0 and args.optimizer == "rowwise_adagrad" and \
-        args.hot_rows_min_workgroups is None
+        args.hot_rows_min_workgroups is None and not args.sort_stream
     traffic = measured_traffic(cfg.name, build_info()) if default_call else None
     io_t = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.io]
     if args.index_dtype == "i32":
@@ -236,8 +239,19 @@ def main():
     torch.cuda.synchronize()
     log(f"inputs ready in {time.time() - t0:.1f}s; nnz/batch ~ {max_nnz}; workspace {ws.numel() / 1e6:.1f} MB")
 
+    side = torch.cuda.Stream() if args.sort_stream else None
+
     def step(k):
         idx, off = batches[k % pool]
+        if side is not None:   # (row-wise AdaGrad, any element types)
+            main_stream = torch.cuda.current_stream()
+            side.wait_stream(main_stream)
+            tbe.backward_prepare(idx, off, cfg.B, ws, stream=side)
+            tbe.forward_ex(flat, idx, off, cfg.B, cfg.pooling, out=out)
+            main_stream.wait_stream(side)
+            tbe.backward_apply_rowwise_adagrad(gouts[k % n_go], off, cfg.B, int(idx.numel()), flat, state, ws,
+                                               pooling=cfg.pooling, lr=cfg.lr, eps=cfg.eps, momentum_scale=cfg.c)
+            return
         if args.optimizer == "sgd":
             tbe.forward_ex(flat, idx, off, cfg.B, cfg.pooling, out=out)
             tbe.backward_sgd(gouts[k % n_go], idx, off, cfg.B, flat, ws, pooling=cfg.pooling, lr=cfg.lr)
@@ -260,6 +274,7 @@ def main():
     run = step
     if args.graph:
         # one graph per distinct (batch, grad_out) pair; the calls record kernels only (no memset, no allocation)
+        assert not args.sort_stream, "--graph and --sort-stream are separate experiments"
         side = torch.cuda.Stream()
         period = pool * n_go // math.gcd(pool, n_go)
         graphs = []
@@ -496,7 +511,7 @@ def main():
                    "lookups_per_step": lookups / max(1, args.steps), "unique_rows_per_lookup":
                        sum(sum(u) for u in U_all) / max(1, sum(nnz_all)), "batch_pool": pool,
                    "lr": cfg.lr, "eps": cfg.eps, "momentum_scale": cfg.c,
-                   "launch": "hip_graph" if args.graph else "eager"},
+                   "launch": "hip_graph" if args.graph else ("eager, sort on a second stream" if args.sort_stream else "eager")},
         "roofline": roofline,
         "roofline_step": roofline_step,
         "roofline_backward": roofline_backward,
