@@ -275,12 +275,12 @@ def main():
     if args.graph:
         # one graph per distinct (batch, grad_out) pair; the calls record kernels only (no memset, no allocation)
         assert not args.sort_stream, "--graph and --sort-stream are separate experiments"
-        side = torch.cuda.Stream()
+        capture_stream = torch.cuda.Stream()
         period = pool * n_go // math.gcd(pool, n_go)
         graphs = []
         for k in range(period):
             g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
+            with torch.cuda.graph(g, stream=capture_stream):
                 step(k)
             graphs.append(g)
         torch.cuda.synchronize()
